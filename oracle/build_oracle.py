@@ -1,0 +1,26 @@
+"""Compiles the CPU oracle (test infrastructure) into oracle/liboracle.so with gcc.
+
+The oracle is plain C; -ffp-contract=off keeps every binary32 operation as
+written (fused multiply-adds only where fmaf() is called).
+"""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB = os.path.join(HERE, "liboracle.so")
+SOURCES = ["mixaq_oracle.c", "uniform_block.c"]
+
+
+def build(force=True):
+    srcs = [os.path.join(HERE, s) for s in SOURCES]
+    deps = srcs + [os.path.join(HERE, "arith.h")]
+    if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
+        return LIB
+    cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-fPIC", "-shared",
+           "-Wall", "-Wextra", "-Wno-maybe-uninitialized", "-o", LIB] + srcs + ["-lm"]
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build())

@@ -1,0 +1,390 @@
+"""Pins of the CPU oracle to things other than itself (all run without a GPU).
+
+Each test names what fixes the expected value: a library routine, a closed
+form, brute force, exact rational arithmetic, or a separately written block.
+"""
+import ctypes as C
+from fractions import Fraction
+
+import numpy as np
+import pytest
+from scipy.special import ndtr
+
+import oracle_api as O
+from float_swin_ref import float_block, sqnr_db
+from paper_2507_19131_amd import synth
+
+L = O.lib()
+
+
+def _arr_fn(fn, v):
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    out = np.empty_like(v)
+    fn(v.ctypes.data_as(O._FP), out.ctypes.data_as(O._FP), C.c_int64(v.size))
+    return out
+
+
+# ---------------------------------------------------------------- scalar arithmetic
+def test_exp2_pinned_against_libm():
+    y = np.linspace(-100.0, 0.0, 2_000_001).astype(np.float32)
+    got = _arr_fn(L.orc_exp2_array, y).astype(np.float64)
+    ref = np.exp2(y.astype(np.float64))
+    assert np.max(np.abs(got / ref - 1.0)) <= 3e-7
+    assert L.orc_exp2(0.0) == pytest.approx(1.0, abs=2e-7)
+    # below the clamp the value of -100 is held (absolute error < 1e-30)
+    assert L.orc_exp2(-1000.0) == L.orc_exp2(-100.0) < 1e-30
+    # exact powers of two scale exactly
+    assert L.orc_exp2(-3.0) == L.orc_exp2(0.0) / 8.0
+
+
+def test_gelu_pinned_against_erf_form():
+    x = np.linspace(-12.0, 12.0, 2_400_001).astype(np.float32)
+    got = _arr_fn(L.orc_gelu_array, x).astype(np.float64)
+    ref = x.astype(np.float64) * ndtr(x.astype(np.float64))
+    assert np.max(np.abs(got - ref)) <= 1e-6
+    big = np.array([20.0, 1e3, 1e6, -20.0, -1e3, -1e6], dtype=np.float32)
+    g = _arr_fn(L.orc_gelu_array, big)
+    assert np.all(np.abs(g[:3] - big[:3]) <= 1e-6) and np.all(np.abs(g[3:]) <= 1e-6)
+
+
+def _q_exact(v, scale, z, bits):
+    """Exact rational evaluation of the quantizer definition."""
+    inv = np.float32(1.0) / np.float32(scale)
+    t = Fraction(float(np.float32(v))) * Fraction(float(inv))
+    fl = t.numerator // t.denominator
+    fr = t - fl
+    n = fl + 1 if fr > Fraction(1, 2) else fl if fr < Fraction(1, 2) else (fl if fl % 2 == 0 else fl + 1)
+    return int(min(max(n + z, -(1 << (bits - 1))), (1 << (bits - 1)) - 1))
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_quantizer_roundtrip_and_exact_rounding(bits):
+    rng = np.random.default_rng(bits)
+    qmin, qmax = -(1 << (bits - 1)), (1 << (bits - 1)) - 1
+    for scale, z in ((0.0371, 0), (0.0033, -3 if bits > 2 else -1), (1.7, qmin), (2.0 ** -6, 1)):
+        scale = float(np.float32(scale))
+        lo, hi = scale * (qmin - z), scale * (qmax - z)
+        v = rng.uniform(lo, hi, size=4000).astype(np.float32)
+        v = v[(v >= np.float32(lo)) & (v <= np.float32(hi))]
+        q = np.array([L.orc_quantize(float(t), scale, z, bits) for t in v])
+        assert q.min() >= qmin and q.max() <= qmax
+        back = scale * (q - z)
+        assert np.max(np.abs(v.astype(np.float64) - back)) <= scale / 2 * (1 + 2.0 ** -20)
+        for t in v[:300]:
+            assert L.orc_quantize(float(t), scale, z, bits) == _q_exact(t, scale, z, bits)
+        # outside the clip range the code saturates
+        assert L.orc_quantize(float(hi + 10 * scale), scale, z, bits) == qmax
+        assert L.orc_quantize(float(lo - 10 * scale), scale, z, bits) == qmin
+        assert L.orc_quantize(1e30, scale, z, bits) == qmax and L.orc_quantize(-1e30, scale, z, bits) == qmin
+    # ties go to the even integer (scale 2^-6 makes v/scale exact)
+    s = 2.0 ** -6
+    assert L.orc_quantize(0.5 * s, s, 0, 8) == 0 and L.orc_quantize(1.5 * s, s, 0, 8) == 2
+    assert L.orc_quantize(2.5 * s, s, 0, 8) == 2 and L.orc_quantize(-0.5 * s, s, 0, 8) == 0
+    assert L.orc_quantize(2.5 * s, s, 1, 8) == 3       # the zero point is added after rounding
+
+
+def test_layernorm_against_numpy():
+    rng = np.random.default_rng(5)
+    for Cc in (96, 128, 384):
+        x = (rng.standard_normal(Cc) * rng.uniform(0.1, 30) + rng.uniform(-5, 5)).astype(np.float32)
+        g = rng.uniform(0.3, 2, Cc).astype(np.float32)
+        b = rng.standard_normal(Cc).astype(np.float32)
+        y = np.empty(Cc, dtype=np.float32)
+        L.orc_layernorm_token(x.ctypes.data_as(O._FP), Cc, g.ctypes.data_as(O._FP), b.ctypes.data_as(O._FP),
+                              C.c_float(1e-5), y.ctypes.data_as(O._FP))
+        xd = x.astype(np.float64)
+        ref = (xd - xd.mean()) / np.sqrt(xd.var() + 1e-5) * g + b
+        assert np.max(np.abs(y - ref)) <= 4e-6 * max(1.0, np.abs(ref).max())
+
+
+def test_keep_count_values():
+    # 0.4*1369 = 547.6 -> 548, 0.4*361 = 144.4 -> 144 (round half up of keep*nW)
+    for nW, keep, k in ((1369, 0.4, 548), (361, 0.4, 144), (1392, 0.5, 696), (96, 0.25, 24), (96, 0.75, 72),
+                        (64, 0.5, 32), (5, 0.5, 3), (10, 0.0, 0), (10, 1.0, 10)):
+        assert O.keep_count(nW, keep) == k == synth.keep_count(nW, keep)
+
+
+# ---------------------------------------------------------------- geometry
+SIZES = [(200, 336), (256, 256), (128, 128), (25, 42), (14, 14), (9, 30)]
+
+
+@pytest.mark.parametrize("H,W", SIZES)
+@pytest.mark.parametrize("shift", [0, 3])
+def test_gather_is_pad_roll_partition(H, W, shift):
+    """Window gather == numpy pad + roll(-s) + reshape partition; scatter inverts it."""
+    spec = synth.BlockSpec(2, H, W, 4, 1, shift=shift)
+    rng = np.random.default_rng(H * 1000 + W + shift)
+    x = rng.standard_normal((2, H, W, 4)).astype(np.float32)
+    nW = O.num_windows(spec)
+    assert nW == spec.nW == (-(-H // 7)) * (-(-W // 7))
+    perm = np.stack([rng.permutation(nW) for _ in range(2)]).astype(np.int32)
+    win, valid = O.gather_windows(spec, x, perm)
+    xp = np.zeros((2, spec.Hp, spec.Wp, 4), dtype=np.float32)
+    xp[:, :H, :W] = x
+    vp = np.zeros((2, spec.Hp, spec.Wp), dtype=np.uint8)
+    vp[:, :H, :W] = 1
+    xr, vr = np.roll(xp, (-shift, -shift), axis=(1, 2)), np.roll(vp, (-shift, -shift), axis=(1, 2))
+    part = xr.reshape(2, spec.Hp // 7, 7, spec.Wp // 7, 7, 4).transpose(0, 1, 3, 2, 4, 5).reshape(2, nW, 49, 4)
+    vpart = vr.reshape(2, spec.Hp // 7, 7, spec.Wp // 7, 7).transpose(0, 1, 3, 2, 4).reshape(2, nW, 49)
+    exp = np.stack([part[b, perm[b]] for b in range(2)]).reshape(2 * nW, 49, 4)
+    expv = np.stack([vpart[b, perm[b]] for b in range(2)]).reshape(2 * nW, 49)
+    assert np.array_equal(win, exp) and np.array_equal(valid, expv)
+    back = O.scatter_windows(spec, win, perm)
+    assert np.array_equal(back, x)
+
+
+def _swin_region_mask(Hp, Wp, ws, s):
+    """Mask from region labels, the way the Swin reference builds it: [nW,49,49] bool (True = masked)."""
+    img = np.zeros((Hp, Wp), dtype=np.int64)
+    cnt = 0
+    for hs in (slice(0, -ws), slice(-ws, -s), slice(-s, None)):
+        for wsl in (slice(0, -ws), slice(-ws, -s), slice(-s, None)):
+            img[hs, wsl] = cnt
+            cnt += 1
+    mw = img.reshape(Hp // ws, ws, Wp // ws, ws).transpose(0, 2, 1, 3).reshape(-1, ws * ws)
+    return mw[:, :, None] != mw[:, None, :]
+
+
+@pytest.mark.parametrize("H,W", [(14, 14), (14, 21), (21, 28), (26, 33), (9, 30)])
+def test_shift_mask_matches_region_labelling(H, W):
+    spec = synth.BlockSpec(1, H, W, 4, 1, shift=3)
+    d = O.make_desc(spec)
+    ref = _swin_region_mask(spec.Hp, spec.Wp, 7, 3)
+    got = np.zeros_like(ref)
+    for w in range(spec.nW):
+        for i in range(49):
+            for j in range(49):
+                got[w, i, j] = L.orc_mask_pair(C.byref(d), w, i, j)
+    assert np.array_equal(got, ref)
+    d0 = O.make_desc(spec, shift=0)
+    assert all(L.orc_mask_pair(C.byref(d0), w, i, 48 - i) == 0 for w in range(spec.nW) for i in range(49))
+
+
+# ---------------------------------------------------------------- score / select
+def test_score_modes_against_numpy_and_closed_form():
+    spec = synth.BlockSpec(2, 20, 30, 32, 1, score_mode=0)
+    inp = synth.make_block_inputs(spec, 3)
+    x = synth.make_feature_map(spec, 3, blobs=True)
+    xp = np.zeros((2, spec.Hp, spec.Wp, 32))
+    xp[:, :20, :30] = x
+    ref = (xp ** 2).reshape(2, spec.Hp // 7, 7, spec.Wp // 7, 7, 32).sum(axis=(2, 4, 5)).reshape(2, -1)
+    got = O.score_windows(inp, x)
+    assert np.allclose(got, ref, rtol=1e-13, atol=0)
+    # the score ignores the block's shift (un-shifted grid of the stage input)
+    assert np.array_equal(got, O.score_windows(inp, x, shift=3))
+    # mode 1 with gamma = 1, beta = 0: every token contributes C*var/(var+eps)
+    spec1 = synth.BlockSpec(2, 20, 30, 32, 1, score_mode=1)
+    inp1 = synth.make_block_inputs(spec1, 3)
+    inp1.shared.score_gamma = np.ones(32, dtype=np.float32)
+    inp1.shared.score_beta = np.zeros(32, dtype=np.float32)
+    var = xp.var(axis=-1)
+    contrib = 32 * var / (var + 1e-5)
+    contrib[:, 20:, :] = 0
+    contrib[:, :, 30:] = 0
+    ref1 = contrib.reshape(2, spec.Hp // 7, 7, spec.Wp // 7, 7).sum(axis=(2, 4)).reshape(2, -1)
+    assert np.allclose(O.score_windows(inp1, x), ref1, rtol=2e-6)
+
+
+def test_selection_against_sort():
+    rng = np.random.default_rng(11)
+    for nW, k in ((1, 0), (1, 1), (17, 5), (96, 48), (360, 180), (50, 0), (50, 50)):
+        sc = rng.standard_normal((3, nW))
+        sc[1, ::3] = sc[1, 0]                       # ties
+        sc[2] = 0.0                                 # all equal
+        for reverse in (0, 1):
+            perm = O.select_windows(sc, k, reverse)
+            for b in range(3):
+                key = sc[b] if reverse else -sc[b]
+                order = np.lexsort((np.arange(nW), key))          # (score desc, index asc)
+                assert np.array_equal(perm[b, :k], np.sort(order[:k]))
+                assert np.array_equal(perm[b, k:], np.sort(order[k:]))
+                assert np.array_equal(np.sort(perm[b]), np.arange(nW))
+
+
+# ---------------------------------------------------------------- whole block
+def _setup(H, W, Cc, heads, shift, seed, Bn=1, blobs=True, bits=(8, 4), wbits=8):
+    spec = synth.BlockSpec(Bn, H, W, Cc, heads, shift=shift, act_bits_high=bits[0], act_bits_low=bits[1], weight_bits=wbits)
+    return spec, synth.make_block_inputs(spec, seed), synth.make_feature_map(spec, seed, blobs=blobs)
+
+
+@pytest.mark.parametrize("H,W,shift", [(28, 35, 0), (26, 33, 3), (14, 14, 3)])
+@pytest.mark.parametrize("bits", [(8, 4), (4, 2)])
+def test_keep_one_and_zero_equal_uniform_block(H, W, shift, bits):
+    """keep 1.0 == uniform high-bit block, keep 0 == uniform low-bit block (separately written)."""
+    spec, inp, x = _setup(H, W, 64, 2, shift, 21, Bn=2, bits=bits, wbits=bits[0])
+    nW = spec.nW
+    y_hi, _ = O.block_forward(inp, x, None, nW)
+    y_lo, _ = O.block_forward(inp, x, None, 0)
+    assert np.array_equal(y_hi, O.uniform_block(inp, x, 0))
+    assert np.array_equal(y_lo, O.uniform_block(inp, x, 1))
+    assert not np.array_equal(y_hi, y_lo)
+
+
+def test_output_invariant_to_window_order():
+    spec, inp, x = _setup(26, 33, 64, 2, 3, 22, Bn=2)
+    nW, k = spec.nW, 7
+    sc = O.score_windows(inp, x)
+    perm = O.select_windows(sc, k)
+    y0, _ = O.block_forward(inp, x, perm, k)
+    rng = np.random.default_rng(0)
+    perm2 = perm.copy()
+    for b in range(2):
+        perm2[b, :k] = rng.permutation(perm[b, :k])
+        perm2[b, k:] = rng.permutation(perm[b, k:])
+    y1, _ = O.block_forward(inp, x, perm2, k, threads=3)
+    assert np.array_equal(y0, y1)
+    y2, _ = O.block_forward(inp, x, None, k, threads=1)      # internal score+select == explicit
+    assert np.array_equal(y0, y2)
+
+
+@pytest.mark.parametrize("H,W,Cc,heads,shift", [(28, 35, 96, 3, 0), (26, 33, 96, 3, 3), (21, 21, 128, 4, 3)])
+def test_close_to_float_swin_block(H, W, Cc, heads, shift):
+    """The 8-bit block tracks a float Swin block (dense masked attention, libm erf)
+    written separately; more low-bit windows can only lower the SQNR."""
+    spec, inp, x = _setup(H, W, Cc, heads, shift, 7)
+    nW = spec.nW
+    sc = O.score_windows(inp, x)
+    sq = []
+    for k in (nW, nW // 2, 0):
+        perm = O.select_windows(sc, k)
+        y, _ = O.block_forward(inp, x, perm, k)
+        brw = np.ones((1, nW), dtype=int)
+        brw[0, perm[0, :k]] = 0
+        yf = float_block(inp, x, brw)
+        sq.append(sqnr_db(yf - x, y - x))          # on the block's own contribution
+    assert sq[0] >= 28.0, sq
+    assert sq[0] > sq[1] > sq[2] >= 5.0, sq
+
+
+def _rn32(fr):
+    """Round a Fraction to the nearest binary32 (ties to even)."""
+    f = np.float32(float(fr))                      # double rounding is repaired below
+    cands = [f, np.nextafter(f, np.float32(np.inf)), np.nextafter(f, np.float32(-np.inf))]
+    best = min(cands, key=lambda c: (abs(Fraction(float(c)) - fr), int(np.float32(c).view(np.uint32)) & 1))
+    return np.float32(best)
+
+
+def test_taps_stage_by_stage():
+    """Every integer stage recomputed from the previous tap with int64 numpy;
+    float->code stages re-evaluated exactly (rational arithmetic) on samples."""
+    spec, inp, x = _setup(19, 24, 64, 2, 3, 23, Bn=2)
+    nW, k = spec.nW, 5
+    perm = O.select_windows(O.score_windows(inp, x), k)
+    y, t = O.block_forward(inp, x, perm, k, want_taps="all")
+    S, Cc, nh, hd = 2 * nW, 64, 2, 32
+    sh = inp.shared
+    br_of_slot = np.array([0 if (g % nW) < k else 1 for g in range(S)])
+    qp = lambda name: np.array([inp.branches[b].q[name] for b in br_of_slot])      # [S,2]
+    i64 = lambda a: a.astype(np.int64)
+    # int GEMMs with zero-point identity sum((a-z)w) = sum(aw) - z*sum(w)
+    z = qp("a_qkv_in")[:, 1].astype(np.int64)[:, None, None]
+    assert np.array_equal(i64(t["acc_qkv"]), (i64(t["a_qkv_in"]) - z) @ i64(sh.w_qkv).T)
+    z = qp("a_proj_in")[:, 1].astype(np.int64)[:, None, None]
+    assert np.array_equal(i64(t["acc_proj"]), (i64(t["a_proj_in"]) - z) @ i64(sh.w_proj).T)
+    z = qp("a_fc1_in")[:, 1].astype(np.int64)[:, None, None]
+    assert np.array_equal(i64(t["acc_fc1"]), (i64(t["a_fc1_in"]) - z) @ i64(sh.w_fc1).T)
+    z = qp("a_fc2_in")[:, 1].astype(np.int64)[:, None, None]
+    assert np.array_equal(i64(t["acc_fc2"]), (i64(t["a_fc2_in"]) - z) @ i64(sh.w_fc2).T)
+    # attention integer products; channel n = which*C + head*hd + dim
+    qkv = i64(t["qkv"]).reshape(S, 49, 3, nh, hd)
+    s_ref = np.einsum("sihd,sjhd->shij", qkv[:, :, 0], qkv[:, :, 1])
+    assert np.array_equal(i64(t["acc_s"]), s_ref)
+    zp = qp("a_p")[:, 1].astype(np.int64)[:, None, None, None]
+    o_ref = np.einsum("shij,sjhd->sihd", i64(t["p"]) - zp, qkv[:, :, 2]).reshape(S, 49, Cc)
+    assert np.array_equal(i64(t["acc_o"]), o_ref)
+    # |acc| bound: K <= 3072 and |a|,|w| <= 128 (+ zero-point shift <= 255) keeps int32 safe
+    assert 3072 * 255 * 128 < 2 ** 31
+    # y is the scatter of y_win; h - shortcut etc. sampled exactly
+    assert np.array_equal(O.scatter_windows(spec, t["y_win"], perm), y)
+    rng = np.random.default_rng(1)
+    f32 = lambda v: Fraction(float(np.float32(v)))
+    for _ in range(400):
+        g, tok = rng.integers(S), rng.integers(49)
+        b = inp.branches[br_of_slot[g]]
+        bits = spec.act_bits_high if br_of_slot[g] == 0 else spec.act_bits_low
+        # qkv epilogue: f = fma(acc, s_a*s_w, bias) -> code
+        n = rng.integers(3 * Cc)
+        m = np.float32(b.q["a_qkv_in"][0]) * sh.s_qkv[n]
+        f = _rn32(Fraction(int(t["acc_qkv"][g, tok, n])) * f32(m) + f32(b.b_qkv[n]))
+        name = ("a_q", "a_k", "a_v")[n // Cc]
+        assert t["qkv"][g, tok, n] == _q_exact(f, b.q[name][0], b.q[name][1], bits)
+        # attention output: o * (s_p*s_v) -> code
+        n = rng.integers(Cc)
+        f = _rn32(Fraction(int(t["acc_o"][g, tok, n])) * f32(np.float32(b.q["a_p"][0]) * np.float32(b.q["a_v"][0])))
+        assert t["a_proj_in"][g, tok, n] == _q_exact(f, *b.q["a_proj_in"], bits)
+        # fc2 epilogue + residual
+        f = _rn32(Fraction(int(t["acc_fc2"][g, tok, n])) * f32(np.float32(b.q["a_fc2_in"][0]) * sh.s_fc2[n]) + f32(b.b_fc2[n]))
+        assert t["y_win"][g, tok, n] == np.float32(f + t["h"][g, tok, n])
+        # fc1 epilogue: GELU evaluated by the pinned routine (itself pinned to erf above)
+        n = rng.integers(4 * Cc)
+        f = _rn32(Fraction(int(t["acc_fc1"][g, tok, n])) * f32(np.float32(b.q["a_fc1_in"][0]) * sh.s_fc1[n]) + f32(b.b_fc1[n]))
+        assert t["a_fc2_in"][g, tok, n] == _q_exact(L.orc_gelu(float(f)), *b.q["a_fc2_in"], bits)
+    # LN1 + quantizer against float64 numpy on the gathered windows: codes may differ by one
+    # only where the float64 value sits within 1e-4 of a rounding boundary
+    win, valid = O.gather_windows(spec, x, perm)
+    for g in rng.integers(S, size=6):
+        b = inp.branches[br_of_slot[g]]
+        bits = spec.act_bits_high if br_of_slot[g] == 0 else spec.act_bits_low
+        w64 = win[g].astype(np.float64)
+        ln = (w64 - w64.mean(-1, keepdims=True)) / np.sqrt(w64.var(-1, keepdims=True) + spec.ln_eps) * b.ln1_gamma + b.ln1_beta
+        ln *= valid[g][:, None]
+        s_, z_ = b.q["a_qkv_in"]
+        tq = ln / s_
+        ref = np.clip(np.rint(tq) + z_, -(1 << (bits - 1)), (1 << (bits - 1)) - 1)
+        near_tie = np.abs(tq - np.floor(tq) - 0.5) < 1e-4
+        assert np.all((ref == t["a_qkv_in"][g]) | near_tie)
+        assert np.all(t["a_qkv_in"][g][valid[g] == 0] == np.clip(z_, -(1 << (bits - 1)), (1 << (bits - 1)) - 1))
+        # LN2 + quantizer from the h tap, same rule
+        h64 = t["h"][g].astype(np.float64)
+        ln = (h64 - h64.mean(-1, keepdims=True)) / np.sqrt(h64.var(-1, keepdims=True) + spec.ln_eps) * b.ln2_gamma + b.ln2_beta
+        s_, z_ = b.q["a_fc1_in"]
+        tq = ln / s_
+        ref = np.clip(np.rint(tq) + z_, -(1 << (bits - 1)), (1 << (bits - 1)) - 1)
+        assert np.all((ref == t["a_fc1_in"][g]) | (np.abs(tq - np.floor(tq) - 0.5) < 1e-4))
+        # logits -> softmax -> P codes from the integer scores, natural-base float64 softmax
+        d = O.make_desc(spec)
+        msk = np.array([[L.orc_mask_pair(C.byref(d), int(perm.reshape(-1)[g]), i, j) for j in range(49)] for i in range(49)])
+        lgt = t["acc_s"][g].astype(np.float64) * (b.q["a_q"][0] * b.q["a_k"][0] / np.sqrt(hd)) + sh.rel_pos_bias - 100.0 * msk
+        e = np.exp(lgt - lgt.max(-1, keepdims=True))
+        tq = e / e.sum(-1, keepdims=True) / b.q["a_p"][0]
+        ref = np.clip(np.rint(tq) + b.q["a_p"][1], -(1 << (bits - 1)), (1 << (bits - 1)) - 1)
+        assert np.all((ref == t["p"][g]) | (np.abs(tq - np.floor(tq) - 0.5) < 2e-3))
+
+
+def test_softmax_rows_and_masked_codes():
+    rng = np.random.default_rng(2)
+    lg = (rng.standard_normal((64, 49)) * 3).astype(np.float32)
+    lg[:, 40:] -= np.float32(100 * 1.4426950408889634)
+    for row in lg:
+        p = np.empty(49, dtype=np.float32)
+        L.orc_softmax2(row.ctypes.data_as(O._FP), 49, p.ctypes.data_as(O._FP))
+        nat = row.astype(np.float64) * np.log(2.0)               # base-2 logits -> natural logits
+        ref = np.exp(nat - nat.max())
+        ref /= ref.sum()
+        assert abs(float(p.astype(np.float64).sum()) - 1.0) <= 1e-6
+        assert np.max(np.abs(p - ref)) <= 5e-7
+        assert np.all(p[40:] < 1e-30)
+    # inside a block: every masked pair carries the code of probability zero
+    spec, inp, x = _setup(14, 21, 32, 1, 3, 24)
+    perm = O.select_windows(O.score_windows(inp, x), 3)
+    _, t = O.block_forward(inp, x, perm, 3, want_taps=("p",))
+    d = O.make_desc(spec)
+    for g in range(spec.nW):
+        zp = inp.branches[0 if g < 3 else 1].q["a_p"][1]
+        m = np.array([[L.orc_mask_pair(C.byref(d), int(perm[0, g]), i, j) for j in range(49)] for i in range(49)], dtype=bool)
+        assert np.all(t["p"][g, 0][m] == zp)
+    assert m.any()
+
+
+def test_error_codes():
+    spec, inp, x = _setup(14, 14, 32, 1, 0, 25)
+    d, sh, br = O.make_desc(spec), O.make_shared(inp.shared), O.make_branches(inp.branches)
+    y = np.zeros_like(x)
+    bad = O.make_desc(spec)
+    bad.act_bits_low = 9
+    assert L.orc_block_forward(C.byref(bad), C.byref(sh), br, x.ctypes.data_as(O._FP), None, 1, y.ctypes.data_as(O._FP), None, 1) == -3
+    bad = O.make_desc(spec)
+    bad.heads = 5
+    assert L.orc_block_forward(C.byref(bad), C.byref(sh), br, x.ctypes.data_as(O._FP), None, 1, y.ctypes.data_as(O._FP), None, 1) == -2
+    assert L.orc_block_forward(C.byref(d), C.byref(sh), br, None, None, 1, y.ctypes.data_as(O._FP), None, 1) == -1
+    assert L.orc_block_forward(C.byref(d), C.byref(sh), br, x.ctypes.data_as(O._FP), None, 99, y.ctypes.data_as(O._FP), None, 1) == -2
