@@ -1,0 +1,153 @@
+/*
+ * mixaq.h -- C ABI of the MI355X (gfx950) implementation of MixA-Q's
+ * Two-Branch Swin Block (paper Sec. 3.2, Fig. 3).
+ *
+ * The block takes a feature map seen as a sequence of 7x7 activation windows,
+ * scores every window by its L2 norm, sends the highest-scoring windows through
+ * a high-precision branch and the rest through a low-precision branch, and
+ * scatters both results back (Sec. 3.2).  The branches own their LayerNorms and
+ * their activation step sizes / zero points; attention and FFN weights and
+ * biases are shared "shadow layers" (Sec. 3.2).  One compression ratio is given
+ * per pair of blocks, regular + shifted (Sec. 3.3); this API speaks of the keep
+ * ratio = 1 - compression ratio and of k_high = windows per image in the high
+ * branch.
+ *
+ * Conventions
+ *   - Every function returns 0 (MIXAQ_OK) or a negative mixaq_status; nothing
+ *     throws or aborts.  mixaq_last_error() gives the message of the calling
+ *     thread's last failure.  Arguments are validated before any launch.
+ *   - "device" pointers are HIP device memory owned by the caller; "host"
+ *     pointers are ordinary memory.  The library allocates device memory only in
+ *     mixaq_block_create (packed weights, tables) and frees it in
+ *     mixaq_block_destroy.  All work is enqueued on `stream` (a hipStream_t
+ *     passed as void*, NULL = default stream) without synchronising.
+ *   - Feature maps are [B,H,W,C] float, channels last, unpadded.  Internally the
+ *     map is zero-padded at the bottom/right to multiples of the window and, when
+ *     shift > 0, rolled by -shift before partitioning and back afterwards.
+ *   - x and y must not overlap.
+ *   - Integer codes live in int8 containers whatever the bit width; a b-bit
+ *     quantizer clamps to [-2^(b-1), 2^(b-1)-1]:  q = clamp(rne(v/scale) + zp).
+ *   - Supported shapes: window 7, head_dim = C/heads = 32, C a multiple of 32,
+ *     shift in {0,..,6} (shift > 0 needs padded height and width >= 14).
+ */
+#ifndef MIXAQ_H
+#define MIXAQ_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MIXAQ_OK = 0,
+    MIXAQ_E_NULL = -1,        /* a required pointer is NULL */
+    MIXAQ_E_SHAPE = -2,       /* unsupported or inconsistent sizes / ratios / scales */
+    MIXAQ_E_BITS = -3,        /* a bit width outside 2..8 */
+    MIXAQ_E_WORKSPACE = -4,   /* workspace too small or misaligned */
+    MIXAQ_E_HIP = -5          /* a HIP runtime call failed */
+} mixaq_status;
+
+/* x_hat = scale * (q - zero_point): step size and zero point of one activation
+ * quantizer (Sec. 3.2 keeps one set per branch). */
+typedef struct { float scale; int32_t zero_point; } mixaq_qparam;
+
+typedef struct {
+    int32_t B, H, W, C;                 /* feature map [B,H,W,C]                                  */
+    int32_t window, shift;              /* 7; 0 for the regular block, 3 for the shifted one       */
+    int32_t heads, mlp_ratio;           /* C/heads must be 32; FFN hidden size = mlp_ratio*C       */
+    int32_t act_bits_high, act_bits_low, weight_bits;   /* 2..8                                    */
+    int32_t score_mode;                 /* 0: L2 norm of x, 1: L2 norm after the scoring LayerNorm */
+    float   ln_eps;
+} mixaq_block_desc;
+
+/* Per-branch parameters, index 0 = high precision, 1 = low precision (Sec. 3.2:
+ * duplicated LayerNorms, independent step sizes and zero points).  The bias
+ * pointers of the two branches may alias (shared in QAT, independent in PTQ,
+ * Sec. 4.3, PTQ setup).  All pointers: device, float.  zero_point of a_q, a_k, a_v must be 0. */
+typedef struct {
+    const float *ln1_gamma, *ln1_beta, *ln2_gamma, *ln2_beta;      /* [C]                 */
+    const float *b_qkv, *b_proj, *b_fc1, *b_fc2;                   /* [3C],[C],[4C],[C]   */
+    mixaq_qparam a_qkv_in, a_q, a_k, a_v, a_p, a_proj_in, a_fc1_in, a_fc2_in;
+} mixaq_branch_params;
+
+/* Parameters shared by the branches (shadow layers).  Weights: device int8 codes,
+ * row-major [out,in], symmetric with one float scale per output channel.
+ * QKV output channel n = which*C + head*32 + dim, which in {q,k,v}. */
+typedef struct {
+    const int8_t *w_qkv, *w_proj, *w_fc1, *w_fc2;     /* [3C,C],[C,C],[4C,C],[C,4C]            */
+    const float  *s_qkv, *s_proj, *s_fc1, *s_fc2;     /* [3C],[C],[4C],[C]                      */
+    const float  *rel_pos_bias;                       /* [heads,49,49], added to the logits     */
+    const float  *score_gamma, *score_beta;           /* [C], used when score_mode == 1         */
+} mixaq_shared_params;
+
+/* Optional device buffers receiving every intermediate of one forward call, for
+ * parity checks.  NULL members are skipped.  All are slot-major: slot
+ * g = b*nW + j is position j of image b in perm; S = B*nW. */
+typedef struct {
+    int8_t  *a_qkv_in;    /* [S,49,C]   codes entering the QKV projection        */
+    int32_t *acc_qkv;     /* [S,49,3C]  accumulators, zero-point corrected       */
+    int8_t  *qkv;         /* [S,49,3C]  q,k,v codes                              */
+    int32_t *acc_s;       /* [S,heads,49,49]  q.k accumulators                   */
+    int8_t  *p;           /* [S,heads,49,49]  attention probability codes        */
+    int32_t *acc_o;       /* [S,49,C]   p.v accumulators, zero-point corrected   */
+    int8_t  *a_proj_in;   /* [S,49,C]                                            */
+    int32_t *acc_proj;    /* [S,49,C]                                            */
+    float   *h;           /* [S,49,C]   after the first residual                 */
+    int8_t  *a_fc1_in;    /* [S,49,C]                                            */
+    int32_t *acc_fc1;     /* [S,49,4C]                                           */
+    int8_t  *a_fc2_in;    /* [S,49,4C]  codes after GELU                         */
+    int32_t *acc_fc2;     /* [S,49,C]                                            */
+    float   *y_win;       /* [S,49,C]   block output before the scatter          */
+} mixaq_taps;
+
+typedef struct mixaq_block mixaq_block;
+
+int mixaq_version(void);
+const char *mixaq_last_error(void);
+
+/* Windows per image of the padded map. */
+int mixaq_num_windows(const mixaq_block_desc *desc, int32_t *nW_per_image);
+/* k_high = floor(keep_ratio*nW + 1/2) clamped to [0,nW] (Sec. 3.3: the ratio is a
+ * proportion of windows). */
+int mixaq_keep_count(int32_t nW, double keep_ratio, int32_t *k_high);
+
+/* Builds a block: validates, copies the quantizer and LayerNorm parameters and
+ * pre-packs the weights into MFMA operand order in library-owned device memory.
+ * The caller's parameter buffers may be released afterwards.  Synchronises
+ * `stream` once before returning. */
+int mixaq_block_create(const mixaq_block_desc *desc, const mixaq_shared_params *shared,
+                       const mixaq_branch_params branch[2], void *stream, mixaq_block **out);
+int mixaq_block_destroy(mixaq_block *blk);
+
+/* Bytes of device workspace mixaq_block_forward needs (any k_high); 256-aligned. */
+int mixaq_block_workspace_bytes(const mixaq_block *blk, size_t *bytes);
+
+/* Importance scores (Sec. 3.2): squared L2 norm of every window of the
+ * UN-shifted grid, over in-bounds tokens.  x: device [B,H,W,C]; scores: device
+ * double [B,nW].  Computed once per stage and shared by its blocks. */
+int mixaq_score_windows(const mixaq_block *blk, const float *x, double *scores, void *stream);
+
+/* Selection (Sec. 3.2): per image, the k_high windows with the highest score
+ * (ties: lower index first) form the high group.  perm: device int32 [B,nW] =
+ * high group then low group, each in ascending window index.  reverse != 0
+ * inverts the order of importance (worst-case window selection of the robustness study, Sec. 4.1). */
+int mixaq_select_windows(const double *scores, int32_t B, int32_t nW, int32_t k_high,
+                         int32_t reverse, int32_t *perm, void *stream);
+
+/* One Two-Branch Swin Block (Fig. 3): gather + per-branch LayerNorm and
+ * quantizers -> int8 windowed attention -> FFN -> residuals -> scatter.
+ * perm: device [B,nW] from mixaq_select_windows (any order inside a group gives
+ * the same y), or NULL to score and select x internally.  y: device [B,H,W,C],
+ * fully overwritten. */
+int mixaq_block_forward(const mixaq_block *blk, const float *x, const int32_t *perm, int32_t k_high,
+                        float *y, void *workspace, size_t workspace_bytes, void *stream);
+/* Same, and also fills the given taps. */
+int mixaq_block_forward_taps(const mixaq_block *blk, const float *x, const int32_t *perm, int32_t k_high,
+                             float *y, void *workspace, size_t workspace_bytes, void *stream,
+                             const mixaq_taps *taps);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

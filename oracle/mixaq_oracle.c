@@ -87,6 +87,8 @@ static int check_desc(const orc_desc *d)
     if (d->B < 1 || d->H < 1 || d->W < 1 || d->C < 1 || d->window < 1) return ORC_E_SHAPE;
     if (d->heads < 1 || d->C % d->heads) return ORC_E_SHAPE;
     if (d->shift < 0 || d->shift >= d->window) return ORC_E_SHAPE;
+    /* the neighbour predicate of the shift mask needs at least two windows per side */
+    if (d->shift > 0 && (padded(d->H, d->window) < 2 * d->window || padded(d->W, d->window) < 2 * d->window)) return ORC_E_SHAPE;
     if (d->mlp_ratio < 1) return ORC_E_SHAPE;
     if (d->act_bits_high < 2 || d->act_bits_high > 8) return ORC_E_BITS;
     if (d->act_bits_low < 2 || d->act_bits_low > 8) return ORC_E_BITS;
@@ -175,7 +177,7 @@ int orc_score_windows(const orc_desc *d, const orc_shared *sh, const float *x, d
 /* Selection (Sec. 3.2): the k_high windows with the highest scores form the
  * high group.  reading: ties go to the lower window index; perm lists the high
  * group then the low group, each in ascending window index.  reverse != 0
- * inverts the importance order (the paper's worst-case experiment, Sec. 4.3). */
+ * inverts the importance order (the worst-case window selection of the robustness study, Sec. 4.1). */
 int orc_select_windows(const double *scores, int32_t B, int32_t nW, int32_t k_high,
                        int32_t reverse, int32_t *perm)
 {

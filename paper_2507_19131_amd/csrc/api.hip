@@ -1,0 +1,461 @@
+// C ABI of the Two-Branch Swin Block library (see include/mixaq.h): validation,
+// parameter packing at create time, workspace layout and the launch sequence.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/mixaq.h"
+#include "kernels.h"
+
+using namespace mixaq;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                                   \
+    do {                                                                                                \
+        hipError_t e_ = (expr);                                                                         \
+        if (e_ != hipSuccess) return fail(MIXAQ_E_HIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+int round_up(int v, int m) { return (v + m - 1) / m * m; }
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+int check_desc(const mixaq_block_desc* d)
+{
+    if (!d) return fail(MIXAQ_E_NULL, "descriptor is NULL");
+    if (d->B < 1 || d->H < 1 || d->W < 1) return fail(MIXAQ_E_SHAPE, "B, H, W must be positive");
+    if (d->window != WS) return fail(MIXAQ_E_SHAPE, "window must be 7 (got %d)", d->window);
+    if (!channels_supported(d->C)) return fail(MIXAQ_E_SHAPE, "C=%d unsupported (96,128,192,256,384,512,768,1024)", d->C);
+    if (d->heads < 1 || d->C != d->heads * HD) return fail(MIXAQ_E_SHAPE, "C/heads must be 32 (C=%d heads=%d)", d->C, d->heads);
+    if (d->shift < 0 || d->shift >= WS) return fail(MIXAQ_E_SHAPE, "shift must be in 0..6");
+    if (d->shift > 0 && (round_up(d->H, WS) < 2 * WS || round_up(d->W, WS) < 2 * WS))
+        return fail(MIXAQ_E_SHAPE, "shift > 0 needs a padded map of at least 14x14");
+    if (d->mlp_ratio < 1 || d->mlp_ratio > 8) return fail(MIXAQ_E_SHAPE, "mlp_ratio must be in 1..8");
+    if (d->act_bits_high < 2 || d->act_bits_high > 8 || d->act_bits_low < 2 || d->act_bits_low > 8 ||
+        d->weight_bits < 2 || d->weight_bits > 8)
+        return fail(MIXAQ_E_BITS, "bit widths must be in 2..8");
+    if (d->score_mode != 0 && d->score_mode != 1) return fail(MIXAQ_E_SHAPE, "score_mode must be 0 or 1");
+    if (!(d->ln_eps > 0.0f)) return fail(MIXAQ_E_SHAPE, "ln_eps must be positive");
+    long long nW = (long long)(round_up(d->H, WS) / WS) * (round_up(d->W, WS) / WS);
+    if (nW > 4096) return fail(MIXAQ_E_SHAPE, "at most 4096 windows per image (got %lld)", nW);
+    if ((long long)d->B * nW * TOK > (1LL << 30)) return fail(MIXAQ_E_SHAPE, "map too large for 32-bit row indexing");
+    return MIXAQ_OK;
+}
+
+QDev make_qdev(mixaq_qparam p, int bits)
+{
+    QDev q;
+    int qmin = -(1 << (bits - 1)), qmax = (1 << (bits - 1)) - 1;
+    q.scale = p.scale;
+    q.zp = p.zero_point;
+    q.inv_s = 1.0f / p.scale;
+    q.lo = RND_MAGIC + (float)(qmin - p.zero_point);
+    q.hi = RND_MAGIC + (float)(qmax - p.zero_point);
+    q.off = p.zero_point - RND_MAGIC_BITS;
+    return q;
+}
+
+// device buffer owned by a block
+template <typename T>
+int upload(std::vector<void*>& owned, const std::vector<T>& host, T** dev)
+{
+    void* p = nullptr;
+    size_t bytes = host.size() * sizeof(T);
+    HIP_TRY(hipMalloc(&p, bytes ? bytes : 16));
+    owned.push_back(p);
+    if (bytes) HIP_TRY(hipMemcpy(p, host.data(), bytes, hipMemcpyHostToDevice));
+    *dev = (T*)p;
+    return MIXAQ_OK;
+}
+
+template <typename T>
+int download(const T* dev, size_t n, std::vector<T>& host)
+{
+    host.resize(n);
+    HIP_TRY(hipMemcpy(host.data(), dev, n * sizeof(T), hipMemcpyDeviceToHost));
+    return MIXAQ_OK;
+}
+
+struct Linear {           // one shadow layer prepared for the device
+    int K = 0, N = 0;
+    v4i* Wp = nullptr;
+    float* m[2] = {nullptr, nullptr};
+    float* bias[2] = {nullptr, nullptr};
+    int* negcorr[2] = {nullptr, nullptr};
+};
+
+}  // namespace
+
+struct mixaq_block {
+    mixaq_block_desc d;
+    int Hp, Wp, nWc, nW;
+    std::vector<void*> owned;
+    Linear qkv, proj, fc1, fc2;
+    float* ln_gamma[2][2];     // [which LN][branch]
+    float* ln_beta[2][2];
+    float* score_gamma = nullptr;
+    float* score_beta = nullptr;
+    float* bias2 = nullptr;
+    QDev q_in[2], q_qkv[2][3], q_p[2], q_ao[2], q_fc1in[2], q_fc2in[2];
+    float m2[2], m_o[2];
+    size_t ws_bytes = 0;
+    int rows_max = 0;
+};
+
+namespace {
+
+// packs W[N,K] (row-major int8) into MFMA A-operand order and builds the per-branch epilogue constants
+int prepare_linear(mixaq_block* blk, Linear& L, const int8_t* w_dev, const float* s_dev, int N, int K,
+                   const float* const bias_dev[2], const mixaq_qparam in_q[2], int weight_bits)
+{
+    std::vector<int8_t> w;
+    std::vector<float> s, b;
+    int rc;
+    if ((rc = download(w_dev, (size_t)N * K, w))) return rc;
+    if ((rc = download(s_dev, (size_t)N, s))) return rc;
+    const int wmax = (1 << (weight_bits - 1)) - 1, wmin = -(1 << (weight_bits - 1));
+    std::vector<int> colsum(N, 0);
+    for (int n = 0; n < N; ++n) {
+        if (!(s[n] > 0.0f) || !std::isfinite(s[n])) return fail(MIXAQ_E_SHAPE, "weight scale %d is not positive", n);
+        for (int k = 0; k < K; ++k) {
+            int v = w[(size_t)n * K + k];
+            if (v < wmin || v > wmax) return fail(MIXAQ_E_BITS, "weight code %d outside the %d-bit range", v, weight_bits);
+            colsum[n] += v;
+        }
+    }
+    const int NB = N / 32, KS = K / 32;
+    std::vector<int8_t> packed((size_t)N * K);
+    for (int nb = 0; nb < NB; ++nb)
+        for (int ks = 0; ks < KS; ++ks)
+            for (int lane = 0; lane < 64; ++lane) {
+                const int8_t* src = &w[(size_t)(nb * 32 + lane % 32) * K + ks * 32 + (lane / 32) * 16];
+                memcpy(&packed[(((size_t)nb * KS + ks) * 64 + lane) * 16], src, 16);
+            }
+    L.K = K;
+    L.N = N;
+    int8_t* wp = nullptr;
+    if ((rc = upload(blk->owned, packed, &wp))) return rc;
+    L.Wp = (v4i*)wp;
+    for (int br = 0; br < 2; ++br) {
+        if ((rc = download(bias_dev[br], (size_t)N, b))) return rc;
+        std::vector<float> m(N);
+        std::vector<int> nc(N);
+        for (int n = 0; n < N; ++n) {
+            m[n] = in_q[br].scale * s[n];
+            nc[n] = -in_q[br].zero_point * colsum[n];
+        }
+        if ((rc = upload(blk->owned, m, &L.m[br]))) return rc;
+        if ((rc = upload(blk->owned, b, &L.bias[br]))) return rc;
+        if ((rc = upload(blk->owned, nc, &L.negcorr[br]))) return rc;
+    }
+    return MIXAQ_OK;
+}
+
+// original padded coordinates of token t of window (wr,wc) in the rolled frame
+void token_src(const mixaq_block* b, int wr, int wc, int t, int* r, int* c)
+{
+    *r = (wr * WS + t / WS + b->d.shift) % b->Hp;
+    *c = (wc * WS + t % WS + b->d.shift) % b->Wp;
+}
+
+int check_qparam(const mixaq_qparam& q, int bits, const char* name)
+{
+    if (!(q.scale > 0.0f) || !std::isfinite(q.scale)) return fail(MIXAQ_E_SHAPE, "%s: scale must be positive", name);
+    if (q.zero_point < -(1 << (bits - 1)) || q.zero_point > (1 << (bits - 1)) - 1)
+        return fail(MIXAQ_E_SHAPE, "%s: zero point outside the %d-bit range", name, bits);
+    return MIXAQ_OK;
+}
+
+void make_geom(const mixaq_block* b, int k_hi, Geom* G)
+{
+    G->B = b->d.B; G->H = b->d.H; G->W = b->d.W; G->C = b->d.C; G->shift = b->d.shift; G->heads = b->d.heads;
+    G->Hp = b->Hp; G->Wp = b->Wp; G->nWc = b->nWc; G->nW = b->nW;
+    G->k_hi = k_hi; G->k_lo = b->nW - k_hi;
+    G->rows_hi = b->d.B * k_hi * TOK;
+    G->rows_lo = b->d.B * G->k_lo * TOK;
+    G->base_lo = round_up(G->rows_hi, ROW_TILE);
+    G->rows_total = G->base_lo + round_up(G->rows_lo, ROW_TILE);
+}
+
+struct Workspace {
+    double* scores; int* perm; int* row_pix; int* row_canon;
+    int8_t *a1, *qkv, *ao, *a2, *g; float* h;
+};
+
+size_t carve(const mixaq_block* b, char* base, Workspace* w)
+{
+    size_t off = 0;
+    const size_t R = b->rows_max, C = b->d.C, S = (size_t)b->d.B * b->nW, F = C * b->d.mlp_ratio;
+    auto take = [&](size_t bytes) { char* p = base ? base + off : nullptr; off += align256(bytes); return p; };
+    w->scores = (double*)take(S * 8);
+    w->perm = (int*)take(S * 4);
+    w->row_pix = (int*)take(R * 4);
+    w->row_canon = (int*)take(R * 4);
+    w->a1 = (int8_t*)take(R * C);
+    w->qkv = (int8_t*)take(R * 3 * C);
+    w->ao = (int8_t*)take(R * C);
+    w->h = (float*)take(R * C * 4);
+    w->a2 = (int8_t*)take(R * C);
+    w->g = (int8_t*)take(R * F);
+    return off;
+}
+
+int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, float* y, void* workspace,
+                 size_t workspace_bytes, void* stream, const mixaq_taps* taps)
+{
+    if (!blk) return fail(MIXAQ_E_NULL, "block is NULL");
+    if (!x || !y) return fail(MIXAQ_E_NULL, "x or y is NULL");
+    if (!workspace) return fail(MIXAQ_E_NULL, "workspace is NULL");
+    if (k_high < 0 || k_high > blk->nW) return fail(MIXAQ_E_SHAPE, "k_high=%d outside 0..%d", k_high, blk->nW);
+    if (workspace_bytes < blk->ws_bytes) return fail(MIXAQ_E_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, blk->ws_bytes);
+    if ((uintptr_t)workspace & 255) return fail(MIXAQ_E_WORKSPACE, "workspace must be 256-byte aligned");
+    {
+        const char *xa = (const char*)x, *ya = (const char*)y;
+        size_t bytes = (size_t)blk->d.B * blk->d.H * blk->d.W * blk->d.C * 4;
+        if (xa < ya + bytes && ya < xa + bytes) return fail(MIXAQ_E_SHAPE, "x and y overlap");
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const mixaq_block_desc& d = blk->d;
+    Geom G;
+    make_geom(blk, k_high, &G);
+    Workspace ws;
+    carve(blk, (char*)workspace, &ws);
+    static const mixaq_taps no_taps = {};
+    const mixaq_taps& tp = taps ? *taps : no_taps;
+
+    if (!perm) {     // score and select here (single-block use)
+        launch_score(G, x, d.score_mode, d.ln_eps, blk->score_gamma, blk->score_beta, ws.scores, st);
+        launch_select(ws.scores, d.B, blk->nW, k_high, 0, ws.perm, st);
+        perm = ws.perm;
+    }
+    // gather + LN1 + quantize
+    LnArgs la = {};
+    la.perm = perm; la.src = x; la.eps = d.ln_eps; la.out = ws.a1; la.row_pix = ws.row_pix; la.row_canon = ws.row_canon;
+    la.tap = tp.a_qkv_in;
+    for (int br = 0; br < 2; ++br) { la.gamma[br] = blk->ln_gamma[0][br]; la.beta[br] = blk->ln_beta[0][br]; la.q[br] = blk->q_in[br]; }
+    launch_ln_quant(G, la, true, st);
+    // QKV projection
+    auto fill = [&](GemmArgs& a, const Linear& L, const int8_t* act) {
+        a = GemmArgs{};
+        a.A = act; a.Wp = L.Wp; a.K = L.K; a.N = L.N;
+        for (int br = 0; br < 2; ++br) { a.m[br] = L.m[br]; a.bias[br] = L.bias[br]; a.negcorr[br] = L.negcorr[br]; }
+        a.row_pix = ws.row_pix; a.row_canon = ws.row_canon;
+    };
+    GemmArgs ga;
+    fill(ga, blk->qkv, ws.a1);
+    for (int br = 0; br < 2; ++br) for (int k = 0; k < 3; ++k) ga.q[br][k] = blk->q_qkv[br][k];
+    ga.out8 = ws.qkv; ga.tap_acc = tp.acc_qkv; ga.tap_code = tp.qkv;
+    launch_gemm(G, ga, EPI_QKV, st);
+    // windowed attention
+    AttnArgs aa = {};
+    aa.qkv = ws.qkv; aa.perm = perm; aa.bias2 = blk->bias2; aa.out = ws.ao;
+    for (int br = 0; br < 2; ++br) { aa.m2[br] = blk->m2[br]; aa.m_o[br] = blk->m_o[br]; aa.qp[br] = blk->q_p[br]; aa.qo[br] = blk->q_ao[br]; }
+    aa.tap_s = tp.acc_s; aa.tap_p = tp.p; aa.tap_o = tp.acc_o; aa.tap_code = tp.a_proj_in;
+    launch_attn(G, aa, st);
+    // output projection + first residual
+    fill(ga, blk->proj, ws.ao);
+    ga.outf = ws.h; ga.x = x; ga.tap_acc = tp.acc_proj; ga.tap_f = tp.h;
+    launch_gemm(G, ga, EPI_PROJ, st);
+    // LN2 + quantize
+    la.perm = nullptr; la.src = ws.h; la.out = ws.a2; la.tap = tp.a_fc1_in;
+    for (int br = 0; br < 2; ++br) { la.gamma[br] = blk->ln_gamma[1][br]; la.beta[br] = blk->ln_beta[1][br]; la.q[br] = blk->q_fc1in[br]; }
+    launch_ln_quant(G, la, false, st);
+    // FFN
+    fill(ga, blk->fc1, ws.a2);
+    for (int br = 0; br < 2; ++br) ga.q[br][0] = blk->q_fc2in[br];
+    ga.out8 = ws.g; ga.tap_acc = tp.acc_fc1; ga.tap_code = tp.a_fc2_in;
+    launch_gemm(G, ga, EPI_FC1, st);
+    fill(ga, blk->fc2, ws.g);
+    ga.resid = ws.h; ga.y = y; ga.tap_acc = tp.acc_fc2; ga.tap_f = tp.y_win;
+    launch_gemm(G, ga, EPI_FC2, st);
+    HIP_TRY(hipGetLastError());
+    return MIXAQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mixaq_version(void) { return 100; }
+
+const char* mixaq_last_error(void) { return g_err; }
+
+int mixaq_num_windows(const mixaq_block_desc* desc, int32_t* nW)
+{
+    int rc = check_desc(desc);
+    if (rc) return rc;
+    if (!nW) return fail(MIXAQ_E_NULL, "nW_per_image is NULL");
+    *nW = (round_up(desc->H, WS) / WS) * (round_up(desc->W, WS) / WS);
+    return MIXAQ_OK;
+}
+
+int mixaq_keep_count(int32_t nW, double keep_ratio, int32_t* k_high)
+{
+    if (!k_high) return fail(MIXAQ_E_NULL, "k_high is NULL");
+    if (nW < 0 || !(keep_ratio >= 0.0) || !(keep_ratio <= 1.0)) return fail(MIXAQ_E_SHAPE, "need nW >= 0 and 0 <= keep_ratio <= 1");
+    double k = std::floor(keep_ratio * (double)nW + 0.5);
+    if (k < 0) k = 0;
+    if (k > nW) k = nW;
+    *k_high = (int32_t)k;
+    return MIXAQ_OK;
+}
+
+int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* sh, const mixaq_branch_params branch[2],
+                       void* stream, mixaq_block** out)
+{
+    int rc = check_desc(desc);
+    if (rc) return rc;
+    if (!sh || !branch || !out) return fail(MIXAQ_E_NULL, "shared, branch or out is NULL");
+    if (!sh->w_qkv || !sh->w_proj || !sh->w_fc1 || !sh->w_fc2 || !sh->s_qkv || !sh->s_proj || !sh->s_fc1 || !sh->s_fc2 ||
+        !sh->rel_pos_bias)
+        return fail(MIXAQ_E_NULL, "a shared parameter pointer is NULL");
+    if (desc->score_mode == 1 && (!sh->score_gamma || !sh->score_beta)) return fail(MIXAQ_E_NULL, "score_mode 1 needs score_gamma/beta");
+    for (int br = 0; br < 2; ++br) {
+        const mixaq_branch_params& p = branch[br];
+        if (!p.ln1_gamma || !p.ln1_beta || !p.ln2_gamma || !p.ln2_beta || !p.b_qkv || !p.b_proj || !p.b_fc1 || !p.b_fc2)
+            return fail(MIXAQ_E_NULL, "a parameter pointer of branch %d is NULL", br);
+        int bits = br == 0 ? desc->act_bits_high : desc->act_bits_low;
+        const mixaq_qparam* q = &p.a_qkv_in;
+        static const char* names[8] = {"a_qkv_in", "a_q", "a_k", "a_v", "a_p", "a_proj_in", "a_fc1_in", "a_fc2_in"};
+        for (int k = 0; k < 8; ++k) if ((rc = check_qparam(q[k], bits, names[k]))) return rc;
+        if (p.a_q.zero_point || p.a_k.zero_point || p.a_v.zero_point) return fail(MIXAQ_E_SHAPE, "zero points of q, k, v must be 0");
+    }
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    mixaq_block* b = new (std::nothrow) mixaq_block();
+    if (!b) return fail(MIXAQ_E_HIP, "out of host memory");
+    b->d = *desc;
+    b->Hp = round_up(desc->H, WS); b->Wp = round_up(desc->W, WS);
+    b->nWc = b->Wp / WS; b->nW = (b->Hp / WS) * b->nWc;
+    const int C = desc->C, F = C * desc->mlp_ratio, heads = desc->heads;
+    auto bail = [&](int code) { mixaq_block_destroy(b); return code; };
+    mixaq_qparam qi[2];
+    const float* bias[2];
+    qi[0] = branch[0].a_qkv_in; qi[1] = branch[1].a_qkv_in; bias[0] = branch[0].b_qkv; bias[1] = branch[1].b_qkv;
+    if ((rc = prepare_linear(b, b->qkv, sh->w_qkv, sh->s_qkv, 3 * C, C, bias, qi, desc->weight_bits))) return bail(rc);
+    qi[0] = branch[0].a_proj_in; qi[1] = branch[1].a_proj_in; bias[0] = branch[0].b_proj; bias[1] = branch[1].b_proj;
+    if ((rc = prepare_linear(b, b->proj, sh->w_proj, sh->s_proj, C, C, bias, qi, desc->weight_bits))) return bail(rc);
+    qi[0] = branch[0].a_fc1_in; qi[1] = branch[1].a_fc1_in; bias[0] = branch[0].b_fc1; bias[1] = branch[1].b_fc1;
+    if ((rc = prepare_linear(b, b->fc1, sh->w_fc1, sh->s_fc1, F, C, bias, qi, desc->weight_bits))) return bail(rc);
+    qi[0] = branch[0].a_fc2_in; qi[1] = branch[1].a_fc2_in; bias[0] = branch[0].b_fc2; bias[1] = branch[1].b_fc2;
+    if ((rc = prepare_linear(b, b->fc2, sh->w_fc2, sh->s_fc2, C, F, bias, qi, desc->weight_bits))) return bail(rc);
+    std::vector<float> tmp;
+    for (int br = 0; br < 2; ++br) {
+        const float* src[4] = {branch[br].ln1_gamma, branch[br].ln1_beta, branch[br].ln2_gamma, branch[br].ln2_beta};
+        float** dst[4] = {&b->ln_gamma[0][br], &b->ln_beta[0][br], &b->ln_gamma[1][br], &b->ln_beta[1][br]};
+        for (int k = 0; k < 4; ++k) {
+            if ((rc = download(src[k], (size_t)C, tmp))) return bail(rc);
+            if ((rc = upload(b->owned, tmp, dst[k]))) return bail(rc);
+        }
+        int bits = br == 0 ? desc->act_bits_high : desc->act_bits_low;
+        b->q_in[br] = make_qdev(branch[br].a_qkv_in, bits);
+        b->q_qkv[br][0] = make_qdev(branch[br].a_q, bits);
+        b->q_qkv[br][1] = make_qdev(branch[br].a_k, bits);
+        b->q_qkv[br][2] = make_qdev(branch[br].a_v, bits);
+        b->q_p[br] = make_qdev(branch[br].a_p, bits);
+        b->q_ao[br] = make_qdev(branch[br].a_proj_in, bits);
+        b->q_fc1in[br] = make_qdev(branch[br].a_fc1_in, bits);
+        b->q_fc2in[br] = make_qdev(branch[br].a_fc2_in, bits);
+        b->m2[br] = ((branch[br].a_q.scale * branch[br].a_k.scale) * (float)(1.0 / std::sqrt((double)HD))) * LOG2E_F;
+        b->m_o[br] = branch[br].a_p.scale * branch[br].a_v.scale;
+    }
+    if (desc->score_mode == 1) {
+        if ((rc = download(sh->score_gamma, (size_t)C, tmp))) return bail(rc);
+        if ((rc = upload(b->owned, tmp, &b->score_gamma))) return bail(rc);
+        if ((rc = download(sh->score_beta, (size_t)C, tmp))) return bail(rc);
+        if ((rc = upload(b->owned, tmp, &b->score_beta))) return bail(rc);
+    }
+    // (relative position bias + shift mask) * log2(e), transposed to [type][head][key][query 64]
+    {
+        std::vector<float> rpb;
+        if ((rc = download(sh->rel_pos_bias, (size_t)heads * TOK * TOK, rpb))) return bail(rc);
+        std::vector<float> tab((size_t)4 * heads * TOK * 64, 0.0f);
+        const int nWr = b->Hp / WS;
+        for (int type = 0; type < 4; ++type) {
+            int wr = (type & 2) ? nWr - 1 : 0, wc = (type & 1) ? b->nWc - 1 : 0;
+            for (int h = 0; h < heads; ++h)
+                for (int i = 0; i < TOK; ++i)
+                    for (int j = 0; j < TOK; ++j) {
+                        float v = rpb[((size_t)h * TOK + i) * TOK + j];
+                        if (desc->shift > 0) {
+                            int ri, ci, rj, cj;
+                            token_src(b, wr, wc, i, &ri, &ci);
+                            token_src(b, wr, wc, j, &rj, &cj);
+                            if (!(std::abs(ri - rj) < WS && std::abs(ci - cj) < WS)) v = v + MASK_VALUE;
+                        }
+                        tab[(((size_t)type * heads + h) * TOK + j) * 64 + i] = v * LOG2E_F;
+                    }
+        }
+        if ((rc = upload(b->owned, tab, &b->bias2))) return bail(rc);
+    }
+    b->rows_max = round_up(desc->B * b->nW * TOK, ROW_TILE) + ROW_TILE;
+    Workspace w;
+    b->ws_bytes = carve(b, nullptr, &w);
+    *out = b;
+    return MIXAQ_OK;
+}
+
+int mixaq_block_destroy(mixaq_block* blk)
+{
+    if (!blk) return MIXAQ_OK;
+    for (void* p : blk->owned) (void)hipFree(p);
+    delete blk;
+    return MIXAQ_OK;
+}
+
+int mixaq_block_workspace_bytes(const mixaq_block* blk, size_t* bytes)
+{
+    if (!blk || !bytes) return fail(MIXAQ_E_NULL, "block or bytes is NULL");
+    *bytes = blk->ws_bytes;
+    return MIXAQ_OK;
+}
+
+int mixaq_score_windows(const mixaq_block* blk, const float* x, double* scores, void* stream)
+{
+    if (!blk || !x || !scores) return fail(MIXAQ_E_NULL, "block, x or scores is NULL");
+    Geom G;
+    make_geom(blk, 0, &G);
+    launch_score(G, x, blk->d.score_mode, blk->d.ln_eps, blk->score_gamma, blk->score_beta, scores, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return MIXAQ_OK;
+}
+
+int mixaq_select_windows(const double* scores, int32_t B, int32_t nW, int32_t k_high, int32_t reverse, int32_t* perm,
+                         void* stream)
+{
+    if (!scores || !perm) return fail(MIXAQ_E_NULL, "scores or perm is NULL");
+    if (B < 1 || nW < 1 || k_high < 0 || k_high > nW) return fail(MIXAQ_E_SHAPE, "need B >= 1, nW >= 1, 0 <= k_high <= nW");
+    if (nW > 4096) return fail(MIXAQ_E_SHAPE, "at most 4096 windows per image");
+    launch_select(scores, B, nW, k_high, reverse ? 1 : 0, perm, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return MIXAQ_OK;
+}
+
+int mixaq_block_forward(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, float* y,
+                        void* workspace, size_t workspace_bytes, void* stream)
+{
+    return forward_impl(blk, x, perm, k_high, y, workspace, workspace_bytes, stream, nullptr);
+}
+
+int mixaq_block_forward_taps(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, float* y,
+                             void* workspace, size_t workspace_bytes, void* stream, const mixaq_taps* taps)
+{
+    return forward_impl(blk, x, perm, k_high, y, workspace, workspace_bytes, stream, taps);
+}
+
+}  // extern "C"

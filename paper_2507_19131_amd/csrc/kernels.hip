@@ -1,0 +1,521 @@
+// gfx950 kernels of the Two-Branch Swin Block (paper Sec. 3.2, Fig. 3):
+//   score_kernel      window importance = squared L2 norm            (Sec. 3.2)
+//   select_kernel     top-k partition into high / low groups         (Sec. 3.2)
+//   ln_quant_kernel   gather (shift folded in) + LayerNorm + quantize, also LN2
+//   gemm_kernel       int8 MFMA linear layers with fused epilogues   (shadow layers)
+//   attn_kernel       per (window, head): QK^T, bias+mask, softmax, P.V
+// Arithmetic that decides an integer code follows the pinned binary32 sequences
+// of mixaq_dev.h; reductions feeding a code run in binary64.
+#include "mixaq_dev.h"
+#include "kernels.h"
+
+namespace mixaq {
+
+// ------------------------------------------------------------------ helpers
+template <int W>
+__device__ __forceinline__ double group_sum(double v)
+{
+#pragma unroll
+    for (int o = W / 2; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// LayerNorm of one token spread over LPT lanes (NV float4 per lane; channel of
+// element e of vector k on lane i: (k*LPT + i)*4 + e).  Mean and variance in
+// binary64, rounded once.
+template <int LPT, int NV>
+__device__ __forceinline__ void token_layernorm(float4 (&v)[NV], int C, float eps, const float* __restrict__ gamma,
+                                                const float* __restrict__ beta, int sub)
+{
+    double s = 0.0;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) s += ((double)v[k].x + (double)v[k].y) + ((double)v[k].z + (double)v[k].w);
+    s = group_sum<LPT>(s);
+    float mean = (float)(s / (double)C);
+    double q = 0.0;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        double a = (double)v[k].x - (double)mean, b = (double)v[k].y - (double)mean;
+        double c = (double)v[k].z - (double)mean, d = (double)v[k].w - (double)mean;
+        q += (a * a + b * b) + (c * c + d * d);
+    }
+    q = group_sum<LPT>(q);
+    float var = (float)(q / (double)C);
+    float rstd = 1.0f / sqrtf(var + eps);
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        int ch = (k * LPT + sub) * 4;
+        float4 g = *(const float4*)(gamma + ch), b = *(const float4*)(beta + ch);
+        v[k].x = fmaf((v[k].x - mean) * rstd, g.x, b.x);
+        v[k].y = fmaf((v[k].y - mean) * rstd, g.y, b.y);
+        v[k].z = fmaf((v[k].z - mean) * rstd, g.z, b.z);
+        v[k].w = fmaf((v[k].w - mean) * rstd, g.w, b.w);
+    }
+}
+
+// ------------------------------------------------------------------ K0 score
+// One workgroup (256 threads) per window of the un-shifted grid.
+template <int LPT, int NV>
+__global__ __launch_bounds__(256) void score_kernel(Geom G, const float* __restrict__ x, int mode, float eps,
+                                                    const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                    double* __restrict__ scores)
+{
+    const int wid = blockIdx.x;                       // b*nW + w
+    const int b = wid / G.nW, w = wid - b * G.nW;
+    const int wr = w / G.nWc, wc = w - wr * G.nWc;
+    const int grp = threadIdx.x / LPT, sub = threadIdx.x % LPT;
+    constexpr int TP = 256 / LPT;
+    double acc = 0.0;
+    for (int t = grp; t < TOK; t += TP) {
+        int pr = wr * WS + t / WS, pc = wc * WS + t % WS;
+        if (pr < G.H && pc < G.W) {                   // uniform inside a token group
+            const float* px = x + ((size_t)(b * G.H + pr) * G.W + pc) * G.C;
+            float4 v[NV];
+#pragma unroll
+            for (int k = 0; k < NV; ++k) v[k] = *(const float4*)(px + (k * LPT + sub) * 4);
+            if (mode == 1) token_layernorm<LPT, NV>(v, G.C, eps, gamma, beta, sub);
+#pragma unroll
+            for (int k = 0; k < NV; ++k)
+                acc += ((double)v[k].x * (double)v[k].x + (double)v[k].y * (double)v[k].y) +
+                       ((double)v[k].z * (double)v[k].z + (double)v[k].w * (double)v[k].w);
+        }
+    }
+    acc = group_sum<64>(acc);
+    __shared__ double part[4];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) scores[wid] = (part[0] + part[1]) + (part[2] + part[3]);
+}
+
+// ------------------------------------------------------------------ K1 select
+// One workgroup (1024 threads) per image: rank by counting under the total order
+// (score descending, index ascending), then a scan places each window in its group.
+__global__ __launch_bounds__(1024) void select_kernel(const double* __restrict__ scores, int nW, int k_hi, int reverse,
+                                                      int* __restrict__ perm)
+{
+    extern __shared__ double sm[];
+    double* sc = sm;                                  // [nW]
+    int* flag = (int*)(sm + nW);                      // [nW]
+    int* wsum = flag + nW;                            // [1024]
+    const int b = blockIdx.x, tid = threadIdx.x;
+    for (int i = tid; i < nW; i += 1024) sc[i] = scores[(size_t)b * nW + i];
+    __syncthreads();
+    for (int w = tid; w < nW; w += 1024) {
+        double sw = sc[w];
+        int rank = 0;
+        for (int v = 0; v < nW; ++v) {
+            double sv = sc[v];
+            bool ahead = reverse ? (sv < sw) : (sv > sw);
+            rank += (ahead || (sv == sw && v < w)) ? 1 : 0;
+        }
+        flag[w] = rank < k_hi ? 1 : 0;
+    }
+    __syncthreads();
+    // exclusive scan of the flags: every thread owns a contiguous chunk
+    const int chunk = (nW + 1023) / 1024;
+    const int lo = min(tid * chunk, nW), hi = min(lo + chunk, nW);
+    int cnt = 0;
+    for (int i = lo; i < hi; ++i) cnt += flag[i];
+    wsum[tid] = cnt;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+        int add = tid >= o ? wsum[tid - o] : 0;
+        __syncthreads();
+        wsum[tid] += add;
+        __syncthreads();
+    }
+    int nh = wsum[tid] - cnt;                         // high windows before this chunk
+    for (int i = lo; i < hi; ++i) {
+        int nl = i - nh;                              // low windows before i
+        if (flag[i]) perm[(size_t)b * nW + nh++] = i;
+        else perm[(size_t)b * nW + k_hi + nl] = i;
+    }
+}
+
+// ------------------------------------------------------------------ K2 / K6
+// One token per group of LPT lanes.  GATHER: source is the feature map through the
+// window / shift / padding index map, and the row bookkeeping is written.
+template <int LPT, int NV, bool GATHER>
+__global__ __launch_bounds__(256) void ln_quant_kernel(Geom G, LnArgs A)
+{
+    constexpr int TP = 256 / LPT;
+    const int row = blockIdx.x * TP + threadIdx.x / LPT, sub = threadIdx.x % LPT;
+    if (row >= G.rows_total) return;
+    int branch, canon, pix;
+    if (GATHER) {
+        RowInfo ri = row_info(G, A.perm, row);
+        branch = ri.branch; canon = ri.canon; pix = ri.pix;
+        if (sub == 0) { A.row_pix[row] = pix; A.row_canon[row] = canon; }
+    } else {
+        branch = row >= G.base_lo ? 1 : 0;
+        canon = A.row_canon[row];
+        pix = 0;
+    }
+    const QDev q = A.q[branch];
+    int8_t* dst = A.out + (size_t)row * G.C;
+    float4 v[NV];
+    const bool real = canon >= 0 && pix >= 0;
+    if (real) {
+        const float* src = GATHER ? A.src + (size_t)pix * G.C : A.src + (size_t)row * G.C;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) v[k] = *(const float4*)(src + (k * LPT + sub) * 4);
+        token_layernorm<LPT, NV>(v, G.C, A.eps, A.gamma[branch], A.beta[branch], sub);
+    } else {
+#pragma unroll
+        for (int k = 0; k < NV; ++k) v[k] = make_float4(0.f, 0.f, 0.f, 0.f);   // padding enters as LN output 0
+    }
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        int code = pack4(quant_code(v[k].x, q), quant_code(v[k].y, q), quant_code(v[k].z, q), quant_code(v[k].w, q));
+        if (canon < 0) code = 0;
+        int ch = (k * LPT + sub) * 4;
+        *(int*)(dst + ch) = code;
+        if (A.tap && canon >= 0) *(int*)(A.tap + (size_t)canon * G.C + ch) = code;
+    }
+}
+
+// ------------------------------------------------------------------ GEMMs
+// out^T = W * act^T on 32x32x32 int8 MFMA: the packed weight fragment is the A
+// operand (rows = output channels), the activation rows are the B operand (columns
+// = tokens), so a lane owns one token and 16 output channels per 32-channel block.
+// A wave computes 64 rows x 32 channels at a time.
+template <int EPI>
+__device__ __forceinline__ void epilogue(const GemmArgs& A, const Geom& G, int branch, int row, int nb, int g,
+                                         const v16i& acc, int pix, int canon)
+{
+    const int N = A.N;
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd) {
+        const int n0 = nb * 32 + qd * 8 + g * 4;
+        const float4 m = *(const float4*)(A.m[branch] + n0);
+        const float4 bs = *(const float4*)(A.bias[branch] + n0);
+        const int a0 = acc[qd * 4 + 0], a1 = acc[qd * 4 + 1], a2 = acc[qd * 4 + 2], a3 = acc[qd * 4 + 3];
+        float f0 = fmaf((float)a0, m.x, bs.x), f1 = fmaf((float)a1, m.y, bs.y);
+        float f2 = fmaf((float)a2, m.z, bs.z), f3 = fmaf((float)a3, m.w, bs.w);
+        if (A.tap_acc && canon >= 0) *(int4*)(A.tap_acc + (size_t)canon * N + n0) = make_int4(a0, a1, a2, a3);
+        if (EPI == EPI_QKV || EPI == EPI_FC1) {
+            if (EPI == EPI_FC1) { f0 = gelu_pinned(f0); f1 = gelu_pinned(f1); f2 = gelu_pinned(f2); f3 = gelu_pinned(f3); }
+            const QDev& q = A.q[branch][EPI == EPI_QKV ? n0 / G.C : 0];
+            int code = pack4(quant_code(f0, q), quant_code(f1, q), quant_code(f2, q), quant_code(f3, q));
+            *(int*)(A.out8 + (size_t)row * N + n0) = code;
+            if (A.tap_code && canon >= 0) *(int*)(A.tap_code + (size_t)canon * N + n0) = code;
+        } else if (EPI == EPI_PROJ) {
+            float4 sc = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (pix >= 0) sc = *(const float4*)(A.x + (size_t)pix * N + n0);
+            float4 o = make_float4(f0 + sc.x, f1 + sc.y, f2 + sc.z, f3 + sc.w);
+            *(float4*)(A.outf + (size_t)row * N + n0) = o;
+            if (A.tap_f && canon >= 0) *(float4*)(A.tap_f + (size_t)canon * N + n0) = o;
+        } else {   // EPI_FC2: second residual and scatter back to the map
+            float4 h = *(const float4*)(A.resid + (size_t)row * N + n0);
+            float4 o = make_float4(f0 + h.x, f1 + h.y, f2 + h.z, f3 + h.w);
+            if (pix >= 0) *(float4*)(A.y + (size_t)pix * N + n0) = o;
+            if (A.tap_f && canon >= 0) *(float4*)(A.tap_f + (size_t)canon * N + n0) = o;
+        }
+    }
+}
+
+template <int KS, int EPI>      // KS = K/32 when the activation fragments fit in registers, 0 = stream them
+__global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 31, g = lane >> 5;
+    const int tile = blockIdx.x * 4 + wave;
+    if (tile * ROW_TILE >= G.rows_total) return;
+    const int row0 = tile * ROW_TILE;
+    const int branch = row0 >= G.base_lo ? 1 : 0;
+    const int K = A.K, ks_n = K / 32, NB = A.N / 32;
+    const int nb_lo = blockIdx.y * A.nb_per_block, nb_hi = min(nb_lo + A.nb_per_block, NB);
+    const int8_t* a0p = A.A + (size_t)(row0 + j) * K + g * 16;
+    const int8_t* a1p = a0p + (size_t)32 * K;
+    int pix[2] = {0, 0}, canon[2];
+    canon[0] = A.row_canon[row0 + j]; canon[1] = A.row_canon[row0 + 32 + j];
+    if (EPI == EPI_PROJ || EPI == EPI_FC2) { pix[0] = A.row_pix[row0 + j]; pix[1] = A.row_pix[row0 + 32 + j]; }
+    v4i b0[KS > 0 ? KS : 1], b1[KS > 0 ? KS : 1];
+    if (KS > 0) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) { b0[ks] = *(const v4i*)(a0p + ks * 32); b1[ks] = *(const v4i*)(a1p + ks * 32); }
+    }
+    for (int nb = nb_lo; nb < nb_hi; ++nb) {
+        v16i c0, c1;
+        {   // accumulators start at -zp_in * colsum(W[n,:])
+            const int* nc = A.negcorr[branch] + nb * 32 + g * 4;
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                int4 t = *(const int4*)(nc + qd * 8);
+                c0[qd * 4 + 0] = t.x; c0[qd * 4 + 1] = t.y; c0[qd * 4 + 2] = t.z; c0[qd * 4 + 3] = t.w;
+            }
+            c1 = c0;
+        }
+        const v4i* wp = A.Wp + (size_t)nb * ks_n * 64 + lane;
+        if (KS > 0) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                v4i w = wp[ks * 64];
+                c0 = mfma32(w, b0[ks], c0);
+                c1 = mfma32(w, b1[ks], c1);
+            }
+        } else {
+#pragma unroll 4
+            for (int ks = 0; ks < ks_n; ++ks) {
+                v4i w = wp[ks * 64];
+                v4i x0 = *(const v4i*)(a0p + ks * 32), x1 = *(const v4i*)(a1p + ks * 32);
+                c0 = mfma32(w, x0, c0);
+                c1 = mfma32(w, x1, c1);
+            }
+        }
+        epilogue<EPI>(A, G, branch, row0 + j, nb, g, c0, pix[0], canon[0]);
+        epilogue<EPI>(A, G, branch, row0 + 32 + j, nb, g, c1, pix[1], canon[1]);
+    }
+}
+
+// ------------------------------------------------------------------ K4 attention
+// One wave per (window slot, head).  S^T = K Q^T (A operand = key rows, B operand =
+// query columns) leaves a lane with one query and the keys in registers, so the
+// softmax reduces in registers; the packed P codes are then directly the B operand
+// of O^T = V^T P^T.  V^T fragments come from a transposing read of V staged in LDS.
+__global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
+{
+    __shared__ __attribute__((aligned(16))) int8_t vs[4][64 * HD];       // V tile per wave, [key][dim]
+    __shared__ __attribute__((aligned(16))) int csum[4][HD];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 31, g = lane >> 5;
+    const int item = blockIdx.x * 4 + wave;                              // slot * heads + head
+    const int n_slots = G.B * G.nW;
+    if (item >= n_slots * G.heads) return;
+    const int slot = item / G.heads, head = item - slot * G.heads;
+    // slot -> region row base, image, position in perm
+    const int n_hi = G.B * G.k_hi;
+    int branch, row0, b, jpos;
+    if (slot < n_hi) { branch = 0; row0 = slot * TOK; b = slot / G.k_hi; jpos = slot - b * G.k_hi; }
+    else { int s = slot - n_hi; branch = 1; row0 = G.base_lo + s * TOK; b = s / G.k_lo; jpos = G.k_hi + s - b * G.k_lo; }
+    const int canon_slot = b * G.nW + jpos;
+    const int w = A.perm[canon_slot];
+    int mtype = 0;
+    if (G.shift > 0) { int wr = w / G.nWc, wc = w - wr * G.nWc; mtype = (wr == G.Hp / WS - 1 ? 2 : 0) + (wc == G.nWc - 1 ? 1 : 0); }
+    const int C3 = 3 * G.C;
+    const int8_t* base = A.qkv + (size_t)row0 * C3 + head * HD + g * 16;
+    const v4i zero4 = {0, 0, 0, 0};
+    v4i qf[2], kf[2];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        int t = tb * 32 + j;
+        qf[tb] = t < TOK ? *(const v4i*)(base + (size_t)t * C3) : zero4;
+        kf[tb] = t < TOK ? *(const v4i*)(base + (size_t)t * C3 + G.C) : zero4;
+        v4i vv = t < TOK ? *(const v4i*)(base + (size_t)t * C3 + 2 * G.C) : zero4;
+        *(v4i*)(&vs[wave][t * HD + g * 16]) = vv;
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __builtin_amdgcn_wave_barrier();
+    // V^T fragments: lane = dim j, byte r of slab kb = V[kb*32 + mfma_row(r,g)][j]; column sums for the zero point of P
+    v4i vt[2];
+    int cs = 0;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        int wd[4];
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            int c[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { c[e] = vs[wave][(kb * 32 + qd * 8 + g * 4 + e) * HD + j]; cs += c[e]; }
+            wd[qd] = pack4(c[0], c[1], c[2], c[3]);
+        }
+        vt[kb] = (v4i){wd[0], wd[1], wd[2], wd[3]};
+    }
+    cs += __shfl_xor(cs, 32, 64);
+    if (g == 0) csum[wave][j] = cs;
+    // S^T tiles [key block][query block]
+    v16i s[2][2];
+    const v16i zero16 = {0};
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int ib = 0; ib < 2; ++ib) s[kb][ib] = mfma32(kf[kb], qf[ib], zero16);
+
+    const QDev qp = A.qp[branch], qo = A.qo[branch];
+    const float m2 = A.m2[branch];
+    const float* bm = A.bias2 + ((size_t)(mtype * G.heads + head) * TOK) * 64;       // [key][query(64)]
+    v16i o[2];
+    v4i pk[2][2];
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib) {
+        const int qi = ib * 32 + j;                                       // this lane's query
+        float lg[2][16];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = kb * 32 + (r >> 2) * 8 + (r & 3);         // + g*4, compile-time part
+                if (key < TOK) {                                          // valid for at least one half
+                    const int kk = key + g * 4;
+                    float v = -INFINITY;
+                    if (kk < TOK) v = fmaf((float)s[kb][ib][r], m2, bm[kk * 64 + qi]);
+                    lg[kb][r] = v;
+                    mx = fmaxf(mx, v);
+                } else lg[kb][r] = -INFINITY;
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        double den = 0.0;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = kb * 32 + (r >> 2) * 8 + (r & 3);
+                if (key < TOK) {
+                    const int kk = key + g * 4;
+                    float e = kk < TOK ? exp2_pinned(lg[kb][r] - mx) : 0.0f;
+                    lg[kb][r] = e;
+                    den += (double)e;
+                }
+            }
+        den += __shfl_xor(den, 32, 64);
+        const float rden = 1.0f / (float)den;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            int wd[4];
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                int c[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int r = qd * 4 + e, key = kb * 32 + qd * 8 + e;
+                    c[e] = 0;
+                    if (key < TOK) {
+                        const int kk = key + g * 4;
+                        if (kk < TOK) {
+                            c[e] = quant_code(lg[kb][r] * rden, qp);
+                            if (qi < TOK) {
+                                size_t ti = (((size_t)canon_slot * G.heads + head) * TOK + qi) * TOK + kk;
+                                if (A.tap_s) A.tap_s[ti] = s[kb][ib][r];
+                                if (A.tap_p) A.tap_p[ti] = (int8_t)c[e];
+                            }
+                        }
+                    }
+                }
+                wd[qd] = pack4(c[0], c[1], c[2], c[3]);
+            }
+            pk[kb][ib] = (v4i){wd[0], wd[1], wd[2], wd[3]};
+        }
+    }
+    // O^T = V^T P^T, minus zp * colsum(V)
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib) {
+        o[ib] = mfma32(vt[0], pk[0][ib], zero16);
+        o[ib] = mfma32(vt[1], pk[1][ib], o[ib]);
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __builtin_amdgcn_wave_barrier();
+    const float m_o = A.m_o[branch];
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib) {
+        const int qi = ib * 32 + j;
+        if (qi < TOK) {
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                const int d0 = qd * 8 + g * 4;
+                const int4 cz = *(const int4*)(&csum[wave][d0]);
+                int a0 = o[ib][qd * 4 + 0] - qp.zp * cz.x, a1 = o[ib][qd * 4 + 1] - qp.zp * cz.y;
+                int a2 = o[ib][qd * 4 + 2] - qp.zp * cz.z, a3 = o[ib][qd * 4 + 3] - qp.zp * cz.w;
+                int code = pack4(quant_code((float)a0 * m_o, qo), quant_code((float)a1 * m_o, qo),
+                                 quant_code((float)a2 * m_o, qo), quant_code((float)a3 * m_o, qo));
+                const int ch = head * HD + d0;
+                *(int*)(A.out + (size_t)(row0 + qi) * G.C + ch) = code;
+                size_t ci = ((size_t)canon_slot * TOK + qi) * G.C + ch;
+                if (A.tap_o) *(int4*)(A.tap_o + ci) = make_int4(a0, a1, a2, a3);
+                if (A.tap_code) *(int*)(A.tap_code + ci) = code;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ launchers
+template <int LPT, int NV>
+static void launch_score_t(const Geom& G, const float* x, int mode, float eps, const float* gm, const float* bt,
+                           double* scores, hipStream_t st)
+{
+    hipLaunchKernelGGL((score_kernel<LPT, NV>), dim3(G.B * G.nW), dim3(256), 0, st, G, x, mode, eps, gm, bt, scores);
+}
+template <int LPT, int NV>
+static void launch_ln_t(const Geom& G, const LnArgs& A, bool gather, hipStream_t st)
+{
+    constexpr int TP = 256 / LPT;
+    dim3 grid((G.rows_total + TP - 1) / TP);
+    if (gather) hipLaunchKernelGGL((ln_quant_kernel<LPT, NV, true>), grid, dim3(256), 0, st, G, A);
+    else hipLaunchKernelGGL((ln_quant_kernel<LPT, NV, false>), grid, dim3(256), 0, st, G, A);
+}
+
+#define MIXAQ_DISPATCH_C(C, CALL)                                             \
+    switch (C) {                                                              \
+        case 96: CALL(8, 3); break;                                           \
+        case 128: CALL(8, 4); break;                                          \
+        case 192: CALL(16, 3); break;                                         \
+        case 256: CALL(16, 4); break;                                         \
+        case 384: CALL(32, 3); break;                                         \
+        case 512: CALL(32, 4); break;                                         \
+        case 768: CALL(64, 3); break;                                         \
+        case 1024: CALL(64, 4); break;                                        \
+        default: return false;                                                \
+    }
+
+bool channels_supported(int C)
+{
+    return C == 96 || C == 128 || C == 192 || C == 256 || C == 384 || C == 512 || C == 768 || C == 1024;
+}
+
+bool launch_score(const Geom& G, const float* x, int mode, float eps, const float* gm, const float* bt, double* scores,
+                  hipStream_t st)
+{
+#define CALL(L, N) launch_score_t<L, N>(G, x, mode, eps, gm, bt, scores, st)
+    MIXAQ_DISPATCH_C(G.C, CALL)
+#undef CALL
+    return true;
+}
+
+void launch_select(const double* scores, int B, int nW, int k_hi, int reverse, int* perm, hipStream_t st)
+{
+    size_t sh = (size_t)nW * 8 + (size_t)nW * 4 + 1024 * 4;
+    hipLaunchKernelGGL(select_kernel, dim3(B), dim3(1024), sh, st, scores, nW, k_hi, reverse, perm);
+}
+
+bool launch_ln_quant(const Geom& G, const LnArgs& A, bool gather, hipStream_t st)
+{
+#define CALL(L, N) launch_ln_t<L, N>(G, A, gather, st)
+    MIXAQ_DISPATCH_C(G.C, CALL)
+#undef CALL
+    return true;
+}
+
+template <int EPI>
+static void launch_gemm_e(const Geom& G, const GemmArgs& A0, hipStream_t st)
+{
+    GemmArgs A = A0;
+    const int tiles = G.rows_total / ROW_TILE, gx = (tiles + 3) / 4, NB = A.N / 32;
+    int split = 1;                                   // split the channel blocks until the grid fills the chip
+    while (gx * split < 1024 && split < NB) ++split;
+    A.nb_per_block = (NB + split - 1) / split;
+    dim3 grid(gx, (NB + A.nb_per_block - 1) / A.nb_per_block);
+    switch (A.K) {
+        case 96: hipLaunchKernelGGL((gemm_kernel<3, EPI>), grid, dim3(256), 0, st, G, A); break;
+        case 128: hipLaunchKernelGGL((gemm_kernel<4, EPI>), grid, dim3(256), 0, st, G, A); break;
+        case 192: hipLaunchKernelGGL((gemm_kernel<6, EPI>), grid, dim3(256), 0, st, G, A); break;
+        case 256: hipLaunchKernelGGL((gemm_kernel<8, EPI>), grid, dim3(256), 0, st, G, A); break;
+        case 384: hipLaunchKernelGGL((gemm_kernel<12, EPI>), grid, dim3(256), 0, st, G, A); break;
+        default: hipLaunchKernelGGL((gemm_kernel<0, EPI>), grid, dim3(256), 0, st, G, A); break;
+    }
+}
+
+void launch_gemm(const Geom& G, const GemmArgs& A, int epi, hipStream_t st)
+{
+    switch (epi) {
+        case EPI_QKV: launch_gemm_e<EPI_QKV>(G, A, st); break;
+        case EPI_PROJ: launch_gemm_e<EPI_PROJ>(G, A, st); break;
+        case EPI_FC1: launch_gemm_e<EPI_FC1>(G, A, st); break;
+        default: launch_gemm_e<EPI_FC2>(G, A, st); break;
+    }
+}
+
+void launch_attn(const Geom& G, const AttnArgs& A, hipStream_t st)
+{
+    const int items = G.B * G.nW * G.heads;
+    hipLaunchKernelGGL(attn_kernel, dim3((items + 3) / 4), dim3(256), 0, st, G, A);
+}
+
+}  // namespace mixaq

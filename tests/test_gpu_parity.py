@@ -1,0 +1,105 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_19131_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+gh = pytest.importorskip("gpu_harness") if torch.cuda.is_available() else None
+
+
+def _case(B, H, W, C, heads, shift, keep, seed, blobs=False, outliers=False, bits=(8, 4), wbits=8, ranges=None, mode=0):
+    spec = synth.BlockSpec(B, H, W, C, heads, shift=shift, act_bits_high=bits[0], act_bits_low=bits[1],
+                           weight_bits=wbits, score_mode=mode)
+    inp = synth.make_block_inputs(spec, seed, ranges=ranges)
+    x = synth.make_feature_map(spec, seed, blobs=blobs, outlier_channels=outliers)
+    return spec, inp, x, synth.keep_count(spec.nW, keep)
+
+
+SMALL = [
+    # B, H, W, C, heads, shift, keep, seed, kwargs
+    (1, 56, 56, 96, 3, 0, 0.5, 1001, {}),                                             # config 1
+    (2, 26, 33, 96, 3, 3, 0.4, 11, dict(blobs=True)),                                 # padded + shifted + batch
+    (2, 20, 27, 128, 4, 3, 0.4, 12, dict(outliers=True, ranges={"a_qkv_in": (-12.0, 13.5), "a_fc1_in": (-11.0, 10.0)})),
+    (1, 14, 21, 192, 6, 3, 0.5, 13, dict(mode=1)),
+    (2, 20, 28, 256, 8, 0, 0.3, 14, {}),
+    (2, 50, 84, 384, 12, 3, 0.25, 1003, {}),                                          # config 3 block
+    (1, 25, 42, 768, 24, 3, 0.5, 1004, dict(bits=(4, 2), wbits=4)),                   # config 4 stage 4
+    (1, 30, 30, 96, 3, 3, 0.0, 15, {}),                                               # everything low
+    (1, 30, 30, 96, 3, 3, 1.0, 16, {}),                                               # everything high
+    (3, 15, 16, 96, 3, 0, 0.11, 17, dict(blobs=True)),                                # one high window per image
+]
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,shift,keep,seed,kw", SMALL)
+def test_block_matches_oracle(B, H, W, C, heads, shift, keep, seed, kw):
+    spec, inp, x, k = _case(B, H, W, C, heads, shift, keep, seed, **kw)
+    print("case", B, H, W, C, heads, shift, keep, seed, kw, flush=True)
+    res = gh.compare_block(inp, x, k)
+    print(res, flush=True)
+    gh.assert_parity(res)
+
+
+@pytest.mark.parametrize("shift", [0, 3])
+def test_config2_full_size(shift):
+    """Swin-T stage 1 at detection scale, the size the benchmark times."""
+    spec, inp, x, k = _case(1, 200, 336, 96, 3, shift, 0.5, 1002, blobs=True)
+    print("config 2 shift", shift, flush=True)
+    res = gh.compare_block(inp, x, k)
+    print(res, flush=True)
+    gh.assert_parity(res)
+
+
+def test_order_invariance_and_reverse_selection():
+    spec, inp, x, k = _case(2, 26, 33, 96, 3, 3, 0.4, 21, blobs=True)
+    dev = torch.device("cuda:0")
+    xt = torch.from_numpy(x).to(dev)
+    import oracle_api as O
+    with gh.GpuBlock(inp) as gb:
+        scores, perm = gb.score_select(xt, k)
+        y0 = gb.forward(xt, perm, k)
+        rng = np.random.default_rng(0)
+        p2 = perm.cpu().numpy().copy()
+        for b in range(2):
+            p2[b, :k] = rng.permutation(p2[b, :k])
+            p2[b, k:] = rng.permutation(p2[b, k:])
+        y1 = gb.forward(xt, torch.from_numpy(p2).to(dev), k)
+        torch.cuda.synchronize()
+        assert torch.equal(y0, y1)
+        _, rperm = gb.score_select(xt, k, reverse=1)
+        assert np.array_equal(rperm.cpu().numpy(), O.select_windows(scores.cpu().numpy(), k, 1))
+
+
+def test_error_paths_do_not_launch():
+    from paper_2507_19131_amd import binding as M
+    spec, inp, x, k = _case(1, 14, 14, 96, 3, 0, 0.5, 22)
+    sh, br = M.to_device(inp)
+    d = M.make_desc(spec)
+    d.act_bits_low = 9
+    with pytest.raises(M.MixaqError) as e:
+        M.mixaq_block_create(d, sh, br)
+    assert e.value.code == -3
+    d = M.make_desc(spec)
+    d.C = 100
+    with pytest.raises(M.MixaqError) as e:
+        M.mixaq_block_create(d, sh, br)
+    assert e.value.code == -2
+    d = M.make_desc(spec, shift=3)
+    d.H = 7
+    with pytest.raises(M.MixaqError):
+        M.mixaq_block_create(d, sh, br)
+    with gh.GpuBlock(inp) as gb:
+        xt = torch.from_numpy(x).cuda()
+        y = torch.empty_like(xt)
+        small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+        with pytest.raises(M.MixaqError) as e:
+            M.mixaq_block_forward(gb.blk, xt, None, k, y, small)
+        assert e.value.code == -4
+        with pytest.raises(M.MixaqError) as e:
+            M.mixaq_block_forward(gb.blk, xt, None, 99, y, gb.ws)
+        assert e.value.code == -2
+        with pytest.raises(M.MixaqError) as e:
+            M.mixaq_block_forward(gb.blk, xt, None, k, xt, gb.ws)
+        assert e.value.code == -2
