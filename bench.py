@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the Two-Branch Swin Block hot path on one MI355X.
+
+One step = one pass of the whole path over the Swin-T stage-1 pair at detection
+scale (BASELINE config 2): score the 1392 windows of a 200x336x96 map once,
+select the high group (keep ratio 0.5), run the regular block and then the
+shifted block (A8 high / A4 low, int8 per-channel weights).  Inputs are seeded
+synthetic tensors already resident in HBM; block creation (weight packing) is
+outside the timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, TOP/s
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, GB/s
+PEAK_VALU_TLOPS = 39.32      # 256 CU x 4 SIMD x 16 lanes x 2.4 GHz, non-packed fp32 lane-ops/s (T)
+
+
+def macs_per_window(C):
+    return 588 * C * C + 4802 * C
+
+
+def kernel_model(name, C, F, heads, n_windows):
+    """Algorithmic work of one launch over n_windows windows: (bound, amount, unit-scale).
+    HBM kernels: bytes; MFMA kernels: int8 ops (2 per MAC)."""
+    T = 49
+    if name == "score":
+        return "hbm", n_windows * (4 * T * C + 8)
+    if name == "select":
+        return "hbm", n_windows * (8 + 4)
+    if name == "gather_ln1_quant":
+        return "hbm", n_windows * (4 * T * C + T * C)
+    if name == "ln2_quant":
+        return "hbm", n_windows * (4 * T * C + T * C)
+    if name == "qkv_gemm":
+        return "mfma", n_windows * 2 * T * C * 3 * C
+    if name == "window_attention":
+        return "mfma", n_windows * 2 * 2 * T * T * C
+    if name == "proj_gemm_residual":
+        return "mfma", n_windows * 2 * T * C * C
+    if name == "fc1_gemm_gelu":
+        return "mfma", n_windows * 2 * T * C * F
+    if name == "fc2_gemm_residual_scatter":
+        return "mfma", n_windows * 2 * T * C * F
+    if name == "window_ln1_qkv_attention":
+        return "mfma", n_windows * 2 * (T * C * 3 * C + 2 * T * T * C)
+    if name == "token_proj_ln2_ffn_scatter":
+        return "mfma", n_windows * 2 * (T * C * C + 2 * T * C * F)
+    raise KeyError(name)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path has no collectives); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2507_19131_amd import binding as M
+    from paper_2507_19131_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    M.load()
+    dev = torch.device("cuda:0")
+    wl = synth.workload("cfg2")
+    stage = wl["stages"][0]
+    spec = stage["spec"]
+    keep = wl["keep"][0]
+    k_high = M.mixaq_keep_count(spec.nW, keep)
+    x_np = synth.make_feature_map(spec, wl["seed"], blobs=wl["blobs"], outlier_channels=wl["outliers"])
+    inputs = [synth.make_block_inputs(spec, wl["seed"] + 10 * i) for i, _ in enumerate(stage["shifts"])]
+    x = torch.from_numpy(x_np).to(dev)
+    blocks = []
+    for inp, shift in zip(inputs, stage["shifts"]):
+        sh, br = M.to_device(inp)
+        blocks.append(M.mixaq_block_create(M.make_desc(spec, shift), sh, br))
+    ws = M.alloc_workspace(blocks[0])
+    scores = torch.empty((spec.B, spec.nW), dtype=torch.float64, device=dev)
+    perm = torch.empty((spec.B, spec.nW), dtype=torch.int32, device=dev)
+    bufs = [torch.empty_like(x), torch.empty_like(x)]
+
+    def step():
+        M.mixaq_score_windows(blocks[0], x, scores)
+        M.mixaq_select_windows(scores, spec.B, spec.nW, k_high, 0, perm)
+        cur = x
+        for i, blk in enumerate(blocks):
+            M.mixaq_block_forward(blk, cur, perm, k_high, bufs[i % 2], ws)
+            cur = bufs[i % 2]
+        return cur
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # per-kernel durations with HIP events on the launch stream, same steps again
+    names = [M.mixaq_kernel_name(i) for i in range(M.NUM_KERNELS)]
+    acc = {n: 0.0 for n in names}
+    launches = {n: 0 for n in names}
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    sel_ms = 0.0
+    for _ in range(args.steps):
+        ev0.record()
+        M.mixaq_score_windows(blocks[0], x, scores)
+        ev1.record()
+        ev1.synchronize()
+        acc["score"] += ev0.elapsed_time(ev1)
+        launches["score"] += 1
+        ev0.record()
+        M.mixaq_select_windows(scores, spec.B, spec.nW, k_high, 0, perm)
+        ev1.record()
+        ev1.synchronize()
+        acc["select"] += ev0.elapsed_time(ev1)
+        launches["select"] += 1
+        cur = x
+        for i, blk in enumerate(blocks):
+            ms = M.mixaq_block_forward_profile(blk, cur, perm, k_high, bufs[i % 2], ws)
+            cur = bufs[i % 2]
+            for n, v in ms.items():
+                if v > 0:
+                    acc[n] += v
+                    launches[n] += 1
+    n_win = spec.B * spec.nW
+    C, F = spec.C, spec.C * spec.mlp_ratio
+    kernels = {}
+    for n in names:
+        if not launches[n]:
+            continue
+        avg_ms = acc[n] / launches[n]
+        bound, amount = kernel_model(n, C, F, spec.heads, n_win)
+        if bound == "hbm":
+            ach, peak, unit = amount / (avg_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
+        else:
+            ach, peak, unit = amount / (avg_ms * 1e-3) / 1e12, PEAK_INT8_TOPS, "TOP/s"
+        kernels[n] = dict(avg_ms=round(avg_ms, 5), launches_per_step=launches[n] // args.steps, bound=bound,
+                          achieved=round(ach, 3), peak=peak, unit=unit, frac=round(ach / peak, 5))
+    per_step = {n: kernels[n]["avg_ms"] * kernels[n]["launches_per_step"] for n in kernels}
+    dom = max(per_step, key=per_step.get)
+    kd = kernels[dom]
+    roofline = dict(kernel=dom, bound=kd["bound"], achieved=kd["achieved"], peak=kd["peak"], unit=kd["unit"],
+                    frac=kd["frac"], traffic=None, avg_ms=kd["avg_ms"])
+
+    windows_per_step = n_win * len(blocks)
+    ops_per_step = 2 * macs_per_window(C) * windows_per_step
+    value = windows_per_step / (ms_per_step * 1e-3)
+    int_tops = ops_per_step / (ms_per_step * 1e-3) / 1e12
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        import oracle_api as O              # the oracle is used for this leg only
+        t0 = time.perf_counter()
+        o_scores = O.score_windows(inputs[0], x_np)
+        o_perm = O.select_windows(o_scores, k_high)
+        cur = x_np
+        for inp, shift in zip(inputs, stage["shifts"]):
+            cur, _ = O.block_forward(inp, cur, o_perm, k_high, shift, threads=1)
+        dt = time.perf_counter() - t0
+        cpu = dict(value=round(windows_per_step / dt, 2), unit="windows/s", cores=1, kind="oracle",
+                   sample="one full step of the same workload (score + select + both blocks, 2784 windows), single thread",
+                   seconds=round(dt, 2), int_tops=round(ops_per_step / dt / 1e12, 5))
+
+    out = dict(metric="windows/sec & effective int-TOPS per two-branch Swin block; % int8 MFMA peak",
+               value=round(value, 1), unit="windows/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=round(ms_per_step, 5), higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="int8 (int32 accumulate, fp32 epilogues)", data="synthetic",
+               config=dict(workload="cfg2: Swin-T stage-1 pair (regular + shifted block), B=1, 200x336x96 padded to 203x336, "
+                                    "1392 windows, 3 heads, keep 0.5, A8/A4, W8", blocks_per_step=len(blocks),
+                           windows_per_step=windows_per_step, k_high=k_high),
+               int_tops=round(int_tops, 3), pct_int8_mfma_peak=round(100 * int_tops / PEAK_INT8_TOPS, 3),
+               ms_per_block=round(ms_per_step / len(blocks), 5),
+               roofline=roofline, kernels=kernels, cpu_baseline=cpu)
+    print(json.dumps(out))
+    for blk in blocks:
+        M.mixaq_block_destroy(blk)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -147,6 +147,24 @@ int mixaq_block_forward_taps(const mixaq_block *blk, const float *x, const int32
                              float *y, void *workspace, size_t workspace_bytes, void *stream,
                              const mixaq_taps *taps);
 
+/* Chooses between the two implementations of the forward call: the fused pair of
+ * kernels (one workgroup per window for gather/LN1/QKV/attention, one per 32-row
+ * tile for proj/LN2/FFN/scatter; the default where supported: C <= 256, mlp_ratio
+ * 4) and the seven-kernel path that handles every supported shape.  Both give the
+ * same bits.  Enabling on an unsupported shape returns MIXAQ_E_SHAPE. */
+int mixaq_block_set_fused(mixaq_block *blk, int32_t enable);
+
+/* Measurement aid for benchmarks (not part of the paper's method): one forward
+ * call with a HIP event before every kernel launch on `stream`; synchronises the
+ * stream and writes the duration of each kernel in milliseconds to the HOST array
+ * kernel_ms[MIXAQ_NUM_KERNELS] (0 for kernels that did not run, e.g. score and
+ * select when perm is given).  mixaq_kernel_name(i) names entry i. */
+#define MIXAQ_NUM_KERNELS 11
+int mixaq_block_forward_profile(const mixaq_block *blk, const float *x, const int32_t *perm, int32_t k_high,
+                                float *y, void *workspace, size_t workspace_bytes, void *stream,
+                                float *kernel_ms);
+const char *mixaq_kernel_name(int32_t i);
+
 #ifdef __cplusplus
 }
 #endif

@@ -72,6 +72,10 @@ def load():
         L.mixaq_block_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                           C.c_size_t, C.c_void_p]
         L.mixaq_block_forward_taps.argtypes = L.mixaq_block_forward.argtypes + [C.c_void_p]
+        L.mixaq_block_forward_profile.argtypes = L.mixaq_block_forward.argtypes + [C.POINTER(C.c_float)]
+        L.mixaq_block_set_fused.argtypes = [C.c_void_p, C.c_int32]
+        L.mixaq_kernel_name.restype = C.c_char_p
+        L.mixaq_kernel_name.argtypes = [C.c_int32]
         _lib = L
     return _lib
 
@@ -161,6 +165,25 @@ def mixaq_block_forward_taps(blk, x, perm, k_high, y, workspace, taps, stream=No
     _check(load().mixaq_block_forward_taps(blk, _ptr(x), _ptr(perm), k_high, _ptr(y), _ptr(workspace),
                                            workspace.numel() * workspace.element_size(), _stream(stream), C.byref(tp)))
     return y
+
+
+NUM_KERNELS = 11
+
+
+def mixaq_block_set_fused(blk, enable):
+    _check(load().mixaq_block_set_fused(blk, int(enable)))
+
+
+def mixaq_kernel_name(i):
+    return load().mixaq_kernel_name(i).decode()
+
+
+def mixaq_block_forward_profile(blk, x, perm, k_high, y, workspace, stream=None):
+    """One forward with HIP events around every kernel; returns {kernel name: milliseconds}."""
+    ms = (C.c_float * NUM_KERNELS)()
+    _check(load().mixaq_block_forward_profile(blk, _ptr(x), _ptr(perm), k_high, _ptr(y), _ptr(workspace),
+                                              workspace.numel() * workspace.element_size(), _stream(stream), ms))
+    return {mixaq_kernel_name(i): float(ms[i]) for i in range(NUM_KERNELS)}
 
 
 # ---------------------------------------------------------------- memory helpers (no arithmetic)

@@ -94,7 +94,8 @@ int download(const T* dev, size_t n, std::vector<T>& host)
 
 struct Linear {           // one shadow layer prepared for the device
     int K = 0, N = 0;
-    v4i* Wp = nullptr;
+    v4i* Wp = nullptr;         // k bytes of a lane half in natural order (operand read from row-major memory)
+    v4i* Wp_reg = nullptr;     // k bytes in the order of MFMA result registers (operand chained from registers)
     float* m[2] = {nullptr, nullptr};
     float* bias[2] = {nullptr, nullptr};
     int* negcorr[2] = {nullptr, nullptr};
@@ -116,13 +117,14 @@ struct mixaq_block {
     float m2[2], m_o[2];
     size_t ws_bytes = 0;
     int rows_max = 0;
+    bool fused = false;        // window + token kernels instead of the seven-kernel path
 };
 
 namespace {
 
 // packs W[N,K] (row-major int8) into MFMA A-operand order and builds the per-branch epilogue constants
 int prepare_linear(mixaq_block* blk, Linear& L, const int8_t* w_dev, const float* s_dev, int N, int K,
-                   const float* const bias_dev[2], const mixaq_qparam in_q[2], int weight_bits)
+                   const float* const bias_dev[2], const mixaq_qparam in_q[2], int weight_bits, bool reg_order)
 {
     std::vector<int8_t> w;
     std::vector<float> s, b;
@@ -152,6 +154,17 @@ int prepare_linear(mixaq_block* blk, Linear& L, const int8_t* w_dev, const float
     int8_t* wp = nullptr;
     if ((rc = upload(blk->owned, packed, &wp))) return rc;
     L.Wp = (v4i*)wp;
+    if (reg_order) {
+        for (int nb = 0; nb < NB; ++nb)
+            for (int ks = 0; ks < KS; ++ks)
+                for (int lane = 0; lane < 64; ++lane)
+                    for (int r = 0; r < 16; ++r) {
+                        int k = ks * 32 + (r / 4) * 8 + (lane / 32) * 4 + r % 4;
+                        packed[(((size_t)nb * KS + ks) * 64 + lane) * 16 + r] = w[(size_t)(nb * 32 + lane % 32) * K + k];
+                    }
+        if ((rc = upload(blk->owned, packed, &wp))) return rc;
+        L.Wp_reg = (v4i*)wp;
+    }
     for (int br = 0; br < 2; ++br) {
         if ((rc = download(bias_dev[br], (size_t)N, b))) return rc;
         std::vector<float> m(N);
@@ -216,8 +229,15 @@ size_t carve(const mixaq_block* b, char* base, Workspace* w)
     return off;
 }
 
+// optional per-kernel timing: one event before every launch and one after the last
+struct Prof {
+    hipEvent_t ev[MIXAQ_NUM_KERNELS + 1];
+    int idx[MIXAQ_NUM_KERNELS + 1];
+    int n = 0;
+};
+
 int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, float* y, void* workspace,
-                 size_t workspace_bytes, void* stream, const mixaq_taps* taps)
+                 size_t workspace_bytes, void* stream, const mixaq_taps* taps, Prof* prof = nullptr)
 {
     if (!blk) return fail(MIXAQ_E_NULL, "block is NULL");
     if (!x || !y) return fail(MIXAQ_E_NULL, "x or y is NULL");
@@ -239,16 +259,52 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, in
     static const mixaq_taps no_taps = {};
     const mixaq_taps& tp = taps ? *taps : no_taps;
 
+    auto mark = [&](int kernel) {
+        if (prof) { prof->idx[prof->n] = kernel; (void)hipEventRecord(prof->ev[prof->n++], st); }
+    };
     if (!perm) {     // score and select here (single-block use)
+        mark(0);
         launch_score(G, x, d.score_mode, d.ln_eps, blk->score_gamma, blk->score_beta, ws.scores, st);
+        mark(1);
         launch_select(ws.scores, d.B, blk->nW, k_high, 0, ws.perm, st);
         perm = ws.perm;
+    }
+    if (blk->fused) {
+        WinArgs wa = {};
+        wa.x = x; wa.perm = perm; wa.eps = d.ln_eps; wa.Wqkv = blk->qkv.Wp; wa.bias2 = blk->bias2; wa.out = ws.ao;
+        wa.row_pix = ws.row_pix; wa.row_canon = ws.row_canon;
+        TokArgs ta = {};
+        ta.ao = ws.ao; ta.x = x; ta.y = y; ta.row_pix = ws.row_pix; ta.row_canon = ws.row_canon; ta.eps = d.ln_eps;
+        ta.Wproj = blk->proj.Wp; ta.W1 = blk->fc1.Wp_reg; ta.W2 = blk->fc2.Wp_reg;
+        for (int br = 0; br < 2; ++br) {
+            wa.gamma[br] = blk->ln_gamma[0][br]; wa.beta[br] = blk->ln_beta[0][br]; wa.q_in[br] = blk->q_in[br];
+            wa.m[br] = blk->qkv.m[br]; wa.bias[br] = blk->qkv.bias[br]; wa.negcorr[br] = blk->qkv.negcorr[br];
+            for (int k = 0; k < 3; ++k) wa.q_qkv[br][k] = blk->q_qkv[br][k];
+            wa.m2[br] = blk->m2[br]; wa.m_o[br] = blk->m_o[br]; wa.qp[br] = blk->q_p[br]; wa.qo[br] = blk->q_ao[br];
+            ta.p_m[br] = blk->proj.m[br]; ta.p_bias[br] = blk->proj.bias[br]; ta.p_negcorr[br] = blk->proj.negcorr[br];
+            ta.f1_m[br] = blk->fc1.m[br]; ta.f1_bias[br] = blk->fc1.bias[br]; ta.f1_negcorr[br] = blk->fc1.negcorr[br];
+            ta.f2_m[br] = blk->fc2.m[br]; ta.f2_bias[br] = blk->fc2.bias[br]; ta.f2_negcorr[br] = blk->fc2.negcorr[br];
+            ta.gamma[br] = blk->ln_gamma[1][br]; ta.beta[br] = blk->ln_beta[1][br];
+            ta.q_fc1in[br] = blk->q_fc1in[br]; ta.q_fc2in[br] = blk->q_fc2in[br];
+        }
+        wa.tap_a1 = tp.a_qkv_in; wa.tap_acc = tp.acc_qkv; wa.tap_qkv = tp.qkv; wa.tap_s = tp.acc_s; wa.tap_p = tp.p;
+        wa.tap_o = tp.acc_o; wa.tap_code = tp.a_proj_in;
+        ta.tap_acc_proj = tp.acc_proj; ta.tap_h = tp.h; ta.tap_a2 = tp.a_fc1_in; ta.tap_acc_fc1 = tp.acc_fc1;
+        ta.tap_g = tp.a_fc2_in; ta.tap_acc_fc2 = tp.acc_fc2; ta.tap_y = tp.y_win;
+        mark(9);
+        launch_window(G, wa, st);
+        mark(10);
+        launch_token(G, ta, st);
+        mark(-1);
+        HIP_TRY(hipGetLastError());
+        return MIXAQ_OK;
     }
     // gather + LN1 + quantize
     LnArgs la = {};
     la.perm = perm; la.src = x; la.eps = d.ln_eps; la.out = ws.a1; la.row_pix = ws.row_pix; la.row_canon = ws.row_canon;
     la.tap = tp.a_qkv_in;
     for (int br = 0; br < 2; ++br) { la.gamma[br] = blk->ln_gamma[0][br]; la.beta[br] = blk->ln_beta[0][br]; la.q[br] = blk->q_in[br]; }
+    mark(2);
     launch_ln_quant(G, la, true, st);
     // QKV projection
     auto fill = [&](GemmArgs& a, const Linear& L, const int8_t* act) {
@@ -261,29 +317,36 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, in
     fill(ga, blk->qkv, ws.a1);
     for (int br = 0; br < 2; ++br) for (int k = 0; k < 3; ++k) ga.q[br][k] = blk->q_qkv[br][k];
     ga.out8 = ws.qkv; ga.tap_acc = tp.acc_qkv; ga.tap_code = tp.qkv;
+    mark(3);
     launch_gemm(G, ga, EPI_QKV, st);
     // windowed attention
     AttnArgs aa = {};
     aa.qkv = ws.qkv; aa.perm = perm; aa.bias2 = blk->bias2; aa.out = ws.ao;
     for (int br = 0; br < 2; ++br) { aa.m2[br] = blk->m2[br]; aa.m_o[br] = blk->m_o[br]; aa.qp[br] = blk->q_p[br]; aa.qo[br] = blk->q_ao[br]; }
     aa.tap_s = tp.acc_s; aa.tap_p = tp.p; aa.tap_o = tp.acc_o; aa.tap_code = tp.a_proj_in;
+    mark(4);
     launch_attn(G, aa, st);
     // output projection + first residual
     fill(ga, blk->proj, ws.ao);
     ga.outf = ws.h; ga.x = x; ga.tap_acc = tp.acc_proj; ga.tap_f = tp.h;
+    mark(5);
     launch_gemm(G, ga, EPI_PROJ, st);
     // LN2 + quantize
     la.perm = nullptr; la.src = ws.h; la.out = ws.a2; la.tap = tp.a_fc1_in;
     for (int br = 0; br < 2; ++br) { la.gamma[br] = blk->ln_gamma[1][br]; la.beta[br] = blk->ln_beta[1][br]; la.q[br] = blk->q_fc1in[br]; }
+    mark(6);
     launch_ln_quant(G, la, false, st);
     // FFN
     fill(ga, blk->fc1, ws.a2);
     for (int br = 0; br < 2; ++br) ga.q[br][0] = blk->q_fc2in[br];
     ga.out8 = ws.g; ga.tap_acc = tp.acc_fc1; ga.tap_code = tp.a_fc2_in;
+    mark(7);
     launch_gemm(G, ga, EPI_FC1, st);
     fill(ga, blk->fc2, ws.g);
     ga.resid = ws.h; ga.y = y; ga.tap_acc = tp.acc_fc2; ga.tap_f = tp.y_win;
+    mark(8);
     launch_gemm(G, ga, EPI_FC2, st);
+    mark(-1);
     HIP_TRY(hipGetLastError());
     return MIXAQ_OK;
 }
@@ -347,13 +410,13 @@ int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* 
     mixaq_qparam qi[2];
     const float* bias[2];
     qi[0] = branch[0].a_qkv_in; qi[1] = branch[1].a_qkv_in; bias[0] = branch[0].b_qkv; bias[1] = branch[1].b_qkv;
-    if ((rc = prepare_linear(b, b->qkv, sh->w_qkv, sh->s_qkv, 3 * C, C, bias, qi, desc->weight_bits))) return bail(rc);
+    if ((rc = prepare_linear(b, b->qkv, sh->w_qkv, sh->s_qkv, 3 * C, C, bias, qi, desc->weight_bits, false))) return bail(rc);
     qi[0] = branch[0].a_proj_in; qi[1] = branch[1].a_proj_in; bias[0] = branch[0].b_proj; bias[1] = branch[1].b_proj;
-    if ((rc = prepare_linear(b, b->proj, sh->w_proj, sh->s_proj, C, C, bias, qi, desc->weight_bits))) return bail(rc);
+    if ((rc = prepare_linear(b, b->proj, sh->w_proj, sh->s_proj, C, C, bias, qi, desc->weight_bits, false))) return bail(rc);
     qi[0] = branch[0].a_fc1_in; qi[1] = branch[1].a_fc1_in; bias[0] = branch[0].b_fc1; bias[1] = branch[1].b_fc1;
-    if ((rc = prepare_linear(b, b->fc1, sh->w_fc1, sh->s_fc1, F, C, bias, qi, desc->weight_bits))) return bail(rc);
+    if ((rc = prepare_linear(b, b->fc1, sh->w_fc1, sh->s_fc1, F, C, bias, qi, desc->weight_bits, true))) return bail(rc);
     qi[0] = branch[0].a_fc2_in; qi[1] = branch[1].a_fc2_in; bias[0] = branch[0].b_fc2; bias[1] = branch[1].b_fc2;
-    if ((rc = prepare_linear(b, b->fc2, sh->w_fc2, sh->s_fc2, C, F, bias, qi, desc->weight_bits))) return bail(rc);
+    if ((rc = prepare_linear(b, b->fc2, sh->w_fc2, sh->s_fc2, C, F, bias, qi, desc->weight_bits, true))) return bail(rc);
     std::vector<float> tmp;
     for (int br = 0; br < 2; ++br) {
         const float* src[4] = {branch[br].ln1_gamma, branch[br].ln1_beta, branch[br].ln2_gamma, branch[br].ln2_beta};
@@ -403,6 +466,7 @@ int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* 
         }
         if ((rc = upload(b->owned, tab, &b->bias2))) return bail(rc);
     }
+    b->fused = fused_supported(C, desc->mlp_ratio);
     b->rows_max = round_up(desc->B * b->nW * TOK, ROW_TILE) + ROW_TILE;
     Workspace w;
     b->ws_bytes = carve(b, nullptr, &w);
@@ -456,6 +520,41 @@ int mixaq_block_forward_taps(const mixaq_block* blk, const float* x, const int32
                              void* workspace, size_t workspace_bytes, void* stream, const mixaq_taps* taps)
 {
     return forward_impl(blk, x, perm, k_high, y, workspace, workspace_bytes, stream, taps);
+}
+
+int mixaq_block_set_fused(mixaq_block* blk, int32_t enable)
+{
+    if (!blk) return fail(MIXAQ_E_NULL, "block is NULL");
+    if (enable && !fused_supported(blk->d.C, blk->d.mlp_ratio))
+        return fail(MIXAQ_E_SHAPE, "the fused kernels need C in {96,128,192,256} and mlp_ratio 4");
+    blk->fused = enable != 0;
+    return MIXAQ_OK;
+}
+
+const char* mixaq_kernel_name(int32_t i)
+{
+    static const char* names[MIXAQ_NUM_KERNELS] = {"score", "select", "gather_ln1_quant", "qkv_gemm", "window_attention",
+                                                   "proj_gemm_residual", "ln2_quant", "fc1_gemm_gelu", "fc2_gemm_residual_scatter",
+                                                   "window_ln1_qkv_attention", "token_proj_ln2_ffn_scatter"};
+    return (i >= 0 && i < MIXAQ_NUM_KERNELS) ? names[i] : "";
+}
+
+int mixaq_block_forward_profile(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, float* y,
+                                void* workspace, size_t workspace_bytes, void* stream, float* kernel_ms)
+{
+    if (!kernel_ms) return fail(MIXAQ_E_NULL, "kernel_ms is NULL");
+    Prof prof;
+    for (int i = 0; i <= MIXAQ_NUM_KERNELS; ++i) HIP_TRY(hipEventCreate(&prof.ev[i]));
+    int rc = forward_impl(blk, x, perm, k_high, y, workspace, workspace_bytes, stream, nullptr, &prof);
+    if (rc == MIXAQ_OK && hipStreamSynchronize((hipStream_t)stream) != hipSuccess) rc = fail(MIXAQ_E_HIP, "stream synchronisation failed");
+    for (int i = 0; i < MIXAQ_NUM_KERNELS; ++i) kernel_ms[i] = 0.0f;
+    if (rc == MIXAQ_OK)
+        for (int i = 0; i + 1 < prof.n; ++i) {
+            float ms = 0.0f;
+            if (hipEventElapsedTime(&ms, prof.ev[i], prof.ev[i + 1]) == hipSuccess) kernel_ms[prof.idx[i]] = ms;
+        }
+    for (int i = 0; i <= MIXAQ_NUM_KERNELS; ++i) (void)hipEventDestroy(prof.ev[i]);
+    return rc;
 }
 
 }  // extern "C"

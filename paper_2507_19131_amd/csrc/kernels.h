@@ -53,7 +53,49 @@ struct AttnArgs {
     int8_t* tap_code;
 };
 
+struct WinArgs {                     // fused window kernel (gather + LN1 + QKV + attention)
+    const float* x;
+    const int* perm;
+    const float* gamma[2];
+    const float* beta[2];
+    float eps;
+    QDev q_in[2];
+    const v4i* Wqkv;                 // packed, natural k order
+    const float* m[2];
+    const float* bias[2];
+    const int* negcorr[2];
+    QDev q_qkv[2][3];
+    const float* bias2;
+    float m2[2], m_o[2];
+    QDev qp[2], qo[2];
+    int8_t* out;                     // attention output codes [rows,C]
+    int* row_pix;
+    int* row_canon;
+    int8_t* tap_a1; int32_t* tap_acc; int8_t* tap_qkv; int32_t* tap_s; int8_t* tap_p; int32_t* tap_o; int8_t* tap_code;
+};
+
+struct TokArgs {                     // fused token kernel (proj + LN2 + FFN + scatter)
+    const int8_t* ao;                // [rows,C]
+    const float* x;
+    float* y;
+    const int* row_pix;
+    const int* row_canon;
+    const v4i* Wproj;                // natural k order
+    const v4i* W1;                   // k order of the MFMA result registers
+    const v4i* W2;
+    const float* p_m[2]; const float* p_bias[2]; const int* p_negcorr[2];
+    const float* f1_m[2]; const float* f1_bias[2]; const int* f1_negcorr[2];
+    const float* f2_m[2]; const float* f2_bias[2]; const int* f2_negcorr[2];
+    const float* gamma[2]; const float* beta[2];
+    float eps;
+    QDev q_fc1in[2], q_fc2in[2];
+    int32_t* tap_acc_proj; float* tap_h; int8_t* tap_a2; int32_t* tap_acc_fc1; int8_t* tap_g; int32_t* tap_acc_fc2; float* tap_y;
+};
+
 bool channels_supported(int C);
+bool fused_supported(int C, int mlp_ratio);
+void launch_window(const Geom& G, const WinArgs& A, hipStream_t st);
+void launch_token(const Geom& G, const TokArgs& A, hipStream_t st);
 bool launch_score(const Geom& G, const float* x, int mode, float eps, const float* gm, const float* bt, double* scores,
                   hipStream_t st);
 void launch_select(const double* scores, int B, int nW, int k_hi, int reverse, int* perm, hipStream_t st);

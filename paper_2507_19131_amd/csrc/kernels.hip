@@ -88,30 +88,36 @@ __global__ __launch_bounds__(256) void score_kernel(Geom G, const float* __restr
 }
 
 // ------------------------------------------------------------------ K1 select
-// One workgroup (1024 threads) per image: rank by counting under the total order
-// (score descending, index ascending), then a scan places each window in its group.
-__global__ __launch_bounds__(1024) void select_kernel(const double* __restrict__ scores, int nW, int k_hi, int reverse,
-                                                      int* __restrict__ perm)
+// Rank by counting under the total order (score descending, index ascending): a window is
+// in the high group iff fewer than k_hi windows are ahead of it.  select_rank_kernel writes
+// that flag into perm; select_place_kernel (one workgroup per image) scans the flags and
+// overwrites perm with the high group then the low group, both in ascending index.
+__global__ __launch_bounds__(256) void select_rank_kernel(const double* __restrict__ scores, int nW, int k_hi, int reverse,
+                                                          int* __restrict__ perm)
 {
-    extern __shared__ double sm[];
-    double* sc = sm;                                  // [nW]
-    int* flag = (int*)(sm + nW);                      // [nW]
-    int* wsum = flag + nW;                            // [1024]
-    const int b = blockIdx.x, tid = threadIdx.x;
-    for (int i = tid; i < nW; i += 1024) sc[i] = scores[(size_t)b * nW + i];
+    extern __shared__ double sc[];                    // [nW]
+    const int b = blockIdx.y, w = blockIdx.x * 256 + threadIdx.x;
+    for (int i = threadIdx.x; i < nW; i += 256) sc[i] = scores[(size_t)b * nW + i];
     __syncthreads();
-    for (int w = tid; w < nW; w += 1024) {
-        double sw = sc[w];
-        int rank = 0;
-        for (int v = 0; v < nW; ++v) {
-            double sv = sc[v];
-            bool ahead = reverse ? (sv < sw) : (sv > sw);
-            rank += (ahead || (sv == sw && v < w)) ? 1 : 0;
-        }
-        flag[w] = rank < k_hi ? 1 : 0;
+    if (w >= nW) return;
+    const double sw = sc[w];
+    int rank = 0;
+    if (reverse) {
+        for (int v = 0; v < nW; ++v) { double sv = sc[v]; rank += (sv < sw || (sv == sw && v < w)) ? 1 : 0; }
+    } else {
+        for (int v = 0; v < nW; ++v) { double sv = sc[v]; rank += (sv > sw || (sv == sw && v < w)) ? 1 : 0; }
     }
+    perm[(size_t)b * nW + w] = rank < k_hi ? 1 : 0;
+}
+
+__global__ __launch_bounds__(1024) void select_place_kernel(int nW, int k_hi, int* __restrict__ perm)
+{
+    extern __shared__ int smi[];
+    int* flag = smi;                                  // [nW]
+    int* wsum = smi + nW;                             // [1024]
+    const int b = blockIdx.x, tid = threadIdx.x;
+    for (int i = tid; i < nW; i += 1024) flag[i] = perm[(size_t)b * nW + i];
     __syncthreads();
-    // exclusive scan of the flags: every thread owns a contiguous chunk
     const int chunk = (nW + 1023) / 1024;
     const int lo = min(tid * chunk, nW), hi = min(lo + chunk, nW);
     int cnt = 0;
@@ -267,72 +273,31 @@ __global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
     }
 }
 
-// ------------------------------------------------------------------ K4 attention
-// One wave per (window slot, head).  S^T = K Q^T (A operand = key rows, B operand =
-// query columns) leaves a lane with one query and the keys in registers, so the
-// softmax reduces in registers; the packed P codes are then directly the B operand
-// of O^T = V^T P^T.  V^T fragments come from a transposing read of V staged in LDS.
-__global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
+// ------------------------------------------------------------------ attention core
+// For one (window, head) held by one wave.  S^T = K Q^T (A operand = key rows, B operand =
+// query columns) leaves a lane with one query per query block and the keys in registers,
+// so the softmax reduces in registers; the packed P codes are then directly the B operand
+// of O^T = V^T P^T.  qf/kf: lane = token tb*32+j, 16 bytes = the lane half's 16 dims (any
+// mapping, the same for q and k).  vt: lane = dim j, byte r of slab kb = V[kb*32 +
+// mfma_row(r,g)][j], zero for keys >= 49.  Returns the raw P.V sums (lane = query, register
+// r = dim mfma_row(r,g)).
+struct AttnCore {
+    const float* bm;          // [49 keys][64 queries] (bias + mask) * log2e of this head and mask type
+    float m2;
+    QDev qp;
+    int32_t* tap_s;           // already offset to this (slot, head): [49][49]
+    int8_t* tap_p;
+};
+
+__device__ __forceinline__ void attention_core(const v4i (&qf)[2], const v4i (&kf)[2], const v4i (&vt)[2],
+                                               const AttnCore& A, int j, int g, v16i (&o)[2])
 {
-    __shared__ __attribute__((aligned(16))) int8_t vs[4][64 * HD];       // V tile per wave, [key][dim]
-    __shared__ __attribute__((aligned(16))) int csum[4][HD];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 31, g = lane >> 5;
-    const int item = blockIdx.x * 4 + wave;                              // slot * heads + head
-    const int n_slots = G.B * G.nW;
-    if (item >= n_slots * G.heads) return;
-    const int slot = item / G.heads, head = item - slot * G.heads;
-    // slot -> region row base, image, position in perm
-    const int n_hi = G.B * G.k_hi;
-    int branch, row0, b, jpos;
-    if (slot < n_hi) { branch = 0; row0 = slot * TOK; b = slot / G.k_hi; jpos = slot - b * G.k_hi; }
-    else { int s = slot - n_hi; branch = 1; row0 = G.base_lo + s * TOK; b = s / G.k_lo; jpos = G.k_hi + s - b * G.k_lo; }
-    const int canon_slot = b * G.nW + jpos;
-    const int w = A.perm[canon_slot];
-    int mtype = 0;
-    if (G.shift > 0) { int wr = w / G.nWc, wc = w - wr * G.nWc; mtype = (wr == G.Hp / WS - 1 ? 2 : 0) + (wc == G.nWc - 1 ? 1 : 0); }
-    const int C3 = 3 * G.C;
-    const int8_t* base = A.qkv + (size_t)row0 * C3 + head * HD + g * 16;
-    const v4i zero4 = {0, 0, 0, 0};
-    v4i qf[2], kf[2];
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-        int t = tb * 32 + j;
-        qf[tb] = t < TOK ? *(const v4i*)(base + (size_t)t * C3) : zero4;
-        kf[tb] = t < TOK ? *(const v4i*)(base + (size_t)t * C3 + G.C) : zero4;
-        v4i vv = t < TOK ? *(const v4i*)(base + (size_t)t * C3 + 2 * G.C) : zero4;
-        *(v4i*)(&vs[wave][t * HD + g * 16]) = vv;
-    }
-    __builtin_amdgcn_s_waitcnt(0);
-    __builtin_amdgcn_wave_barrier();
-    // V^T fragments: lane = dim j, byte r of slab kb = V[kb*32 + mfma_row(r,g)][j]; column sums for the zero point of P
-    v4i vt[2];
-    int cs = 0;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-        int wd[4];
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd) {
-            int c[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { c[e] = vs[wave][(kb * 32 + qd * 8 + g * 4 + e) * HD + j]; cs += c[e]; }
-            wd[qd] = pack4(c[0], c[1], c[2], c[3]);
-        }
-        vt[kb] = (v4i){wd[0], wd[1], wd[2], wd[3]};
-    }
-    cs += __shfl_xor(cs, 32, 64);
-    if (g == 0) csum[wave][j] = cs;
-    // S^T tiles [key block][query block]
-    v16i s[2][2];
     const v16i zero16 = {0};
+    v16i s[2][2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int ib = 0; ib < 2; ++ib) s[kb][ib] = mfma32(kf[kb], qf[ib], zero16);
-
-    const QDev qp = A.qp[branch], qo = A.qo[branch];
-    const float m2 = A.m2[branch];
-    const float* bm = A.bias2 + ((size_t)(mtype * G.heads + head) * TOK) * 64;       // [key][query(64)]
-    v16i o[2];
     v4i pk[2][2];
 #pragma unroll
     for (int ib = 0; ib < 2; ++ib) {
@@ -343,14 +308,14 @@ __global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int key = kb * 32 + (r >> 2) * 8 + (r & 3);         // + g*4, compile-time part
+                const int key = kb * 32 + (r >> 2) * 8 + (r & 3);         // + g*4
+                float v = -INFINITY;
                 if (key < TOK) {                                          // valid for at least one half
                     const int kk = key + g * 4;
-                    float v = -INFINITY;
-                    if (kk < TOK) v = fmaf((float)s[kb][ib][r], m2, bm[kk * 64 + qi]);
-                    lg[kb][r] = v;
+                    if (kk < TOK) v = fmaf((float)s[kb][ib][r], A.m2, A.bm[kk * 64 + qi]);
                     mx = fmaxf(mx, v);
-                } else lg[kb][r] = -INFINITY;
+                }
+                lg[kb][r] = v;
             }
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         double den = 0.0;
@@ -381,11 +346,10 @@ __global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
                     if (key < TOK) {
                         const int kk = key + g * 4;
                         if (kk < TOK) {
-                            c[e] = quant_code(lg[kb][r] * rden, qp);
+                            c[e] = quant_code(lg[kb][r] * rden, A.qp);
                             if (qi < TOK) {
-                                size_t ti = (((size_t)canon_slot * G.heads + head) * TOK + qi) * TOK + kk;
-                                if (A.tap_s) A.tap_s[ti] = s[kb][ib][r];
-                                if (A.tap_p) A.tap_p[ti] = (int8_t)c[e];
+                                if (A.tap_s) A.tap_s[qi * TOK + kk] = s[kb][ib][r];
+                                if (A.tap_p) A.tap_p[qi * TOK + kk] = (int8_t)c[e];
                             }
                         }
                     }
@@ -395,15 +359,19 @@ __global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
             pk[kb][ib] = (v4i){wd[0], wd[1], wd[2], wd[3]};
         }
     }
-    // O^T = V^T P^T, minus zp * colsum(V)
 #pragma unroll
     for (int ib = 0; ib < 2; ++ib) {
         o[ib] = mfma32(vt[0], pk[0][ib], zero16);
         o[ib] = mfma32(vt[1], pk[1][ib], o[ib]);
     }
-    __builtin_amdgcn_s_waitcnt(0);
-    __builtin_amdgcn_wave_barrier();
-    const float m_o = A.m_o[branch];
+}
+
+// zero-point correction, dequantization and requantization of the P.V sums; writes the codes
+// of head `head` for the window's tokens to out[row0 + token][C] (and the taps).
+__device__ __forceinline__ void attention_store(const v16i (&o)[2], const int* csum, const QDev& qp, const QDev& qo, float m_o,
+                                                int j, int g, int head, int C, int8_t* out, int row0, int32_t* tap_o,
+                                                int8_t* tap_code, size_t canon_row0)
+{
 #pragma unroll
     for (int ib = 0; ib < 2; ++ib) {
         const int qi = ib * 32 + j;
@@ -411,16 +379,399 @@ __global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 const int d0 = qd * 8 + g * 4;
-                const int4 cz = *(const int4*)(&csum[wave][d0]);
+                const int4 cz = *(const int4*)(csum + d0);
                 int a0 = o[ib][qd * 4 + 0] - qp.zp * cz.x, a1 = o[ib][qd * 4 + 1] - qp.zp * cz.y;
                 int a2 = o[ib][qd * 4 + 2] - qp.zp * cz.z, a3 = o[ib][qd * 4 + 3] - qp.zp * cz.w;
                 int code = pack4(quant_code((float)a0 * m_o, qo), quant_code((float)a1 * m_o, qo),
                                  quant_code((float)a2 * m_o, qo), quant_code((float)a3 * m_o, qo));
                 const int ch = head * HD + d0;
-                *(int*)(A.out + (size_t)(row0 + qi) * G.C + ch) = code;
-                size_t ci = ((size_t)canon_slot * TOK + qi) * G.C + ch;
-                if (A.tap_o) *(int4*)(A.tap_o + ci) = make_int4(a0, a1, a2, a3);
-                if (A.tap_code) *(int*)(A.tap_code + ci) = code;
+                *(int*)(out + (size_t)(row0 + qi) * C + ch) = code;
+                size_t ci = (canon_row0 + qi) * C + ch;
+                if (tap_o) *(int4*)(tap_o + ci) = make_int4(a0, a1, a2, a3);
+                if (tap_code) *(int*)(tap_code + ci) = code;
+            }
+        }
+    }
+}
+
+// slot (high group of all images first, then the low group) -> branch, first row, canonical slot
+__device__ __forceinline__ void slot_info(const Geom& G, int slot, int& branch, int& row0, int& canon_slot)
+{
+    const int n_hi = G.B * G.k_hi;
+    if (slot < n_hi) { int b = slot / G.k_hi; branch = 0; row0 = slot * TOK; canon_slot = b * G.nW + (slot - b * G.k_hi); }
+    else { int s = slot - n_hi, b = s / G.k_lo; branch = 1; row0 = G.base_lo + s * TOK; canon_slot = b * G.nW + G.k_hi + (s - b * G.k_lo); }
+}
+
+__device__ __forceinline__ int mask_type(const Geom& G, int w)
+{
+    if (G.shift == 0) return 0;
+    int wr = w / G.nWc, wc = w - wr * G.nWc;
+    return (wr == G.Hp / WS - 1 ? 2 : 0) + (wc == G.nWc - 1 ? 1 : 0);
+}
+
+// ------------------------------------------------------------------ K4 attention (unfused path)
+// One wave per (window slot, head); q, k, v codes come from the row-major QKV buffer, V^T
+// fragments from a transposing read of V staged in LDS.
+__global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
+{
+    __shared__ __attribute__((aligned(16))) int8_t vs[4][64 * HD];       // V tile per wave, [key][dim]
+    __shared__ __attribute__((aligned(16))) int csum[4][HD];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 31, g = lane >> 5;
+    const int item = blockIdx.x * 4 + wave;                              // slot * heads + head
+    if (item >= G.B * G.nW * G.heads) return;
+    const int slot = item / G.heads, head = item - slot * G.heads;
+    int branch, row0, canon_slot;
+    slot_info(G, slot, branch, row0, canon_slot);
+    const int mtype = mask_type(G, A.perm[canon_slot]);
+    const int C3 = 3 * G.C;
+    const int8_t* base = A.qkv + (size_t)row0 * C3 + head * HD + g * 16;
+    const v4i zero4 = {0, 0, 0, 0};
+    v4i qf[2], kf[2];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        int t = tb * 32 + j;
+        qf[tb] = t < TOK ? *(const v4i*)(base + (size_t)t * C3) : zero4;
+        kf[tb] = t < TOK ? *(const v4i*)(base + (size_t)t * C3 + G.C) : zero4;
+        v4i vv = t < TOK ? *(const v4i*)(base + (size_t)t * C3 + 2 * G.C) : zero4;
+        *(v4i*)(&vs[wave][t * HD + g * 16]) = vv;
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __builtin_amdgcn_wave_barrier();
+    v4i vt[2];
+    int cs = 0;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        int wd[4];
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            int c[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { c[e] = vs[wave][(kb * 32 + qd * 8 + g * 4 + e) * HD + j]; cs += c[e]; }
+            wd[qd] = pack4(c[0], c[1], c[2], c[3]);
+        }
+        vt[kb] = (v4i){wd[0], wd[1], wd[2], wd[3]};
+    }
+    cs += __shfl_xor(cs, 32, 64);
+    if (g == 0) csum[wave][j] = cs;
+    AttnCore core;
+    core.bm = A.bias2 + ((size_t)(mtype * G.heads + head) * TOK) * 64;
+    core.m2 = A.m2[branch];
+    core.qp = A.qp[branch];
+    const size_t tb = ((size_t)canon_slot * G.heads + head) * TOK * TOK;
+    core.tap_s = A.tap_s ? A.tap_s + tb : nullptr;
+    core.tap_p = A.tap_p ? A.tap_p + tb : nullptr;
+    v16i o[2];
+    attention_core(qf, kf, vt, core, j, g, o);
+    __builtin_amdgcn_s_waitcnt(0);
+    __builtin_amdgcn_wave_barrier();
+    attention_store(o, csum[wave], core.qp, A.qo[branch], A.m_o[branch], j, g, head, G.C, A.out, row0, A.tap_o, A.tap_code,
+                    (size_t)canon_slot * TOK);
+}
+
+// ------------------------------------------------------------------ fused window kernel
+// One workgroup per window slot, one wave per head (NH = C/32 waves):
+//   gather (shift folded into the index map) + LN1 + quantize, shared through LDS as MFMA
+//   fragments -> per head: q, k (transposed product, lane = token) and v (plain product, lane =
+//   dim) straight into operand registers -> attention core -> codes of the attention output.
+template <int NH>
+struct WinCfg {
+    static constexpr int LPT = NH == 3 ? 2 : (NH == 8 ? 8 : 4);     // lanes per token in the LN phase (49 tokens fit one pass)
+    static constexpr int NV = NH * 32 / (4 * LPT);
+};
+
+template <int NH>
+__global__ __launch_bounds__(NH * 64) void window_kernel(Geom G, WinArgs A)
+{
+    constexpr int C = NH * 32, KS = NH, LPT = WinCfg<NH>::LPT, NV = WinCfg<NH>::NV, NT = NH * 64;
+    static_assert(NT / LPT >= TOK, "one pass must cover the window");
+    __shared__ v4i a1s[2 * KS * 64];                                     // LN1 codes as fragments [token block][k slab][lane]
+    __shared__ __attribute__((aligned(16))) int csum[NH][HD];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, g = lane >> 5;
+    int branch, row0, canon_slot;
+    slot_info(G, blockIdx.x, branch, row0, canon_slot);
+    const int w = A.perm[canon_slot];
+    const int bimg = canon_slot / G.nW;
+    int* a1w = (int*)a1s;
+    // dword index of (token slot s, channel c with c%4==0) in the fragment layout (k = channel, natural order)
+    auto frag_dw = [&](int s, int c) { return ((((s >> 5) * KS + (c >> 5)) * 64 + ((c & 31) >> 4) * 32 + (s & 31)) << 2) + ((c & 15) >> 2); };
+    for (int i = tid; i < 15 * (C / 4); i += NT) a1w[frag_dw(TOK + i / (C / 4), (i % (C / 4)) * 4)] = 0;
+    {
+        const int t = tid / LPT, sub = tid % LPT;
+        if (t < TOK) {
+            const int wr = w / G.nWc, wc = w - wr * G.nWc, tr = t / WS, tc = t - tr * WS;
+            int pr = wr * WS + tr + G.shift; if (pr >= G.Hp) pr -= G.Hp;
+            int pc = wc * WS + tc + G.shift; if (pc >= G.Wp) pc -= G.Wp;
+            const int pix = (pr < G.H && pc < G.W) ? (bimg * G.H + pr) * G.W + pc : -1;
+            const int canon = canon_slot * TOK + t;
+            if (sub == 0) { A.row_pix[row0 + t] = pix; A.row_canon[row0 + t] = canon; }
+            float4 v[NV];
+            if (pix >= 0) {
+                const float* src = A.x + (size_t)pix * C;
+#pragma unroll
+                for (int k = 0; k < NV; ++k) v[k] = *(const float4*)(src + (k * LPT + sub) * 4);
+                token_layernorm<LPT, NV>(v, C, A.eps, A.gamma[branch], A.beta[branch], sub);
+            } else {
+#pragma unroll
+                for (int k = 0; k < NV; ++k) v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            const QDev q = A.q_in[branch];
+#pragma unroll
+            for (int k = 0; k < NV; ++k) {
+                const int ch = (k * LPT + sub) * 4;
+                int code = pack4(quant_code(v[k].x, q), quant_code(v[k].y, q), quant_code(v[k].z, q), quant_code(v[k].w, q));
+                a1w[frag_dw(t, ch)] = code;
+                if (A.tap_a1) *(int*)(A.tap_a1 + (size_t)canon * C + ch) = code;
+            }
+        }
+    }
+    __syncthreads();
+    const int head = wave;
+    v4i bf[2][KS];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) bf[tb][ks] = a1s[(tb * KS + ks) * 64 + lane];
+    const size_t canon_row0 = (size_t)canon_slot * TOK;
+    v4i qk[2][2];                                                        // [q|k][token block]
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+        const int nb = which * NH + head;
+        const v4i* wp = A.Wqkv + (size_t)nb * KS * 64 + lane;
+        v4i wf[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) wf[ks] = wp[ks * 64];
+        const QDev qq = A.q_qkv[branch][which];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            v16i acc;
+            const int* nc = A.negcorr[branch] + nb * 32 + g * 4;
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                int4 t4 = *(const int4*)(nc + qd * 8);
+                acc[qd * 4 + 0] = t4.x; acc[qd * 4 + 1] = t4.y; acc[qd * 4 + 2] = t4.z; acc[qd * 4 + 3] = t4.w;
+            }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) acc = mfma32(wf[ks], bf[tb][ks], acc);
+            int wd[4];
+            const int tok = tb * 32 + j;
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                const int n0 = nb * 32 + qd * 8 + g * 4;
+                const float4 m = *(const float4*)(A.m[branch] + n0), bs = *(const float4*)(A.bias[branch] + n0);
+                const int a0 = acc[qd * 4 + 0], a1 = acc[qd * 4 + 1], a2 = acc[qd * 4 + 2], a3 = acc[qd * 4 + 3];
+                wd[qd] = pack4(quant_code(fmaf((float)a0, m.x, bs.x), qq), quant_code(fmaf((float)a1, m.y, bs.y), qq),
+                               quant_code(fmaf((float)a2, m.z, bs.z), qq), quant_code(fmaf((float)a3, m.w, bs.w), qq));
+                if (tok < TOK) {
+                    if (A.tap_acc) *(int4*)(A.tap_acc + (canon_row0 + tok) * (3 * C) + n0) = make_int4(a0, a1, a2, a3);
+                    if (A.tap_qkv) *(int*)(A.tap_qkv + (canon_row0 + tok) * (3 * C) + n0) = wd[qd];
+                }
+            }
+            qk[which][tb] = (v4i){wd[0], wd[1], wd[2], wd[3]};
+        }
+    }
+    v4i vt[2];
+    {
+        const int nb = 2 * NH + head, n = nb * 32 + j;                   // this lane's output channel (dim j of the head)
+        const v4i* wp = A.Wqkv + (size_t)nb * KS * 64 + lane;
+        v4i wf[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) wf[ks] = wp[ks * 64];
+        const float m = A.m[branch][n], bs = A.bias[branch][n];
+        const int nc = A.negcorr[branch][n];
+        const QDev qv = A.q_qkv[branch][2];
+        int cs = 0;
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            v16i acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = nc;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) acc = mfma32(bf[tb][ks], wf[ks], acc);          // rows = tokens, columns = dims
+            int wd[4];
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                int c[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int tok = tb * 32 + qd * 8 + g * 4 + e;
+                    c[e] = 0;
+                    if (tb * 32 + qd * 8 + e < TOK) {
+                        if (tok < TOK) {
+                            c[e] = quant_code(fmaf((float)acc[qd * 4 + e], m, bs), qv);
+                            if (A.tap_acc) A.tap_acc[(canon_row0 + tok) * (3 * C) + n] = acc[qd * 4 + e];
+                            if (A.tap_qkv) A.tap_qkv[(canon_row0 + tok) * (3 * C) + n] = (int8_t)c[e];
+                        }
+                    }
+                    cs += c[e];
+                }
+                wd[qd] = pack4(c[0], c[1], c[2], c[3]);
+            }
+            vt[tb] = (v4i){wd[0], wd[1], wd[2], wd[3]};
+        }
+        cs += __shfl_xor(cs, 32, 64);
+        if (g == 0) csum[wave][j] = cs;
+    }
+    AttnCore core;
+    core.bm = A.bias2 + ((size_t)(mask_type(G, w) * NH + head) * TOK) * 64;
+    core.m2 = A.m2[branch];
+    core.qp = A.qp[branch];
+    const size_t tbase = ((size_t)canon_slot * NH + head) * TOK * TOK;
+    core.tap_s = A.tap_s ? A.tap_s + tbase : nullptr;
+    core.tap_p = A.tap_p ? A.tap_p + tbase : nullptr;
+    v16i o[2];
+    attention_core(qk[0], qk[1], vt, core, j, g, o);
+    __builtin_amdgcn_s_waitcnt(0);
+    __builtin_amdgcn_wave_barrier();
+    attention_store(o, csum[wave], core.qp, A.qo[branch], A.m_o[branch], j, g, head, C, A.out, row0, A.tap_o, A.tap_code, canon_row0);
+}
+
+// ------------------------------------------------------------------ fused token kernel
+// One workgroup per tile of 32 gathered rows, one wave per 32-channel block (NH = C/32 waves):
+//   proj + first residual (wave w owns channels 32w..32w+31, h stays in registers) -> LN2 with
+//   statistics exchanged through LDS -> quantize -> FC1 (each wave 4 hidden blocks) + GELU +
+//   quantize, codes to LDS as fragments -> FC2 + second residual -> scatter to the map.
+template <int NH>
+__global__ __launch_bounds__(NH * 64) void token_kernel(Geom G, TokArgs A)
+{
+    constexpr int C = NH * 32, KS = NH, HB = 4 * NH, F = 4 * C;
+    __shared__ v4i a2s[KS * 64];
+    __shared__ v4i gs[HB * 64];
+    __shared__ double part[2][NH][32];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, g = lane >> 5;
+    const int row = blockIdx.x * 32 + j;
+    const int branch = row >= G.base_lo ? 1 : 0;
+    const bool valid = branch ? (row - G.base_lo < G.rows_lo) : (row < G.rows_hi);
+    const int pix = valid ? A.row_pix[row] : -1;
+    const size_t canon = valid ? (size_t)A.row_canon[row] : 0;
+    const bool tap_ok = valid;
+    const int nb = wave;
+    float h[16];
+    {   // output projection + first residual
+        v16i acc;
+        const int* nc = A.p_negcorr[branch] + nb * 32 + g * 4;
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            int4 t4 = *(const int4*)(nc + qd * 8);
+            acc[qd * 4 + 0] = t4.x; acc[qd * 4 + 1] = t4.y; acc[qd * 4 + 2] = t4.z; acc[qd * 4 + 3] = t4.w;
+        }
+        const int8_t* ap = A.ao + (size_t)row * C + g * 16;
+        const v4i* wp = A.Wproj + (size_t)nb * KS * 64 + lane;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) acc = mfma32(wp[ks * 64], *(const v4i*)(ap + ks * 32), acc);
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            const int n0 = nb * 32 + qd * 8 + g * 4;
+            const float4 m = *(const float4*)(A.p_m[branch] + n0), bs = *(const float4*)(A.p_bias[branch] + n0);
+            float4 sc = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (pix >= 0) sc = *(const float4*)(A.x + (size_t)pix * C + n0);
+            h[qd * 4 + 0] = fmaf((float)acc[qd * 4 + 0], m.x, bs.x) + sc.x;
+            h[qd * 4 + 1] = fmaf((float)acc[qd * 4 + 1], m.y, bs.y) + sc.y;
+            h[qd * 4 + 2] = fmaf((float)acc[qd * 4 + 2], m.z, bs.z) + sc.z;
+            h[qd * 4 + 3] = fmaf((float)acc[qd * 4 + 3], m.w, bs.w) + sc.w;
+            if (tap_ok) {
+                if (A.tap_acc_proj) *(int4*)(A.tap_acc_proj + canon * C + n0) = make_int4(acc[qd * 4], acc[qd * 4 + 1], acc[qd * 4 + 2], acc[qd * 4 + 3]);
+                if (A.tap_h) *(float4*)(A.tap_h + canon * C + n0) = make_float4(h[qd * 4], h[qd * 4 + 1], h[qd * 4 + 2], h[qd * 4 + 3]);
+            }
+        }
+    }
+    {   // LN2: binary64 partial sums per (wave, token) through LDS, then normalise and quantize
+        double s = 0.0;
+#pragma unroll
+        for (int r = 0; r < 16; r += 4) s += ((double)h[r] + (double)h[r + 1]) + ((double)h[r + 2] + (double)h[r + 3]);
+        s += __shfl_xor(s, 32, 64);
+        if (g == 0) part[0][wave][j] = s;
+        __syncthreads();
+        double tot = 0.0;
+#pragma unroll
+        for (int w2 = 0; w2 < NH; ++w2) tot += part[0][w2][j];
+        const float mean = (float)(tot / (double)C);
+        double q = 0.0;
+#pragma unroll
+        for (int r = 0; r < 16; r += 4) {
+            double a = (double)h[r] - (double)mean, b = (double)h[r + 1] - (double)mean;
+            double c = (double)h[r + 2] - (double)mean, d = (double)h[r + 3] - (double)mean;
+            q += (a * a + b * b) + (c * c + d * d);
+        }
+        q += __shfl_xor(q, 32, 64);
+        if (g == 0) part[1][wave][j] = q;
+        __syncthreads();
+        tot = 0.0;
+#pragma unroll
+        for (int w2 = 0; w2 < NH; ++w2) tot += part[1][w2][j];
+        const float var = (float)(tot / (double)C);
+        const float rstd = 1.0f / sqrtf(var + A.eps);
+        const QDev qa = A.q_fc1in[branch];
+        int wd[4];
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            const int n0 = nb * 32 + qd * 8 + g * 4;
+            const float4 gm = *(const float4*)(A.gamma[branch] + n0), bt = *(const float4*)(A.beta[branch] + n0);
+            wd[qd] = pack4(quant_code(fmaf((h[qd * 4 + 0] - mean) * rstd, gm.x, bt.x), qa),
+                           quant_code(fmaf((h[qd * 4 + 1] - mean) * rstd, gm.y, bt.y), qa),
+                           quant_code(fmaf((h[qd * 4 + 2] - mean) * rstd, gm.z, bt.z), qa),
+                           quant_code(fmaf((h[qd * 4 + 3] - mean) * rstd, gm.w, bt.w), qa));
+            if (tap_ok && A.tap_a2) *(int*)(A.tap_a2 + canon * C + n0) = wd[qd];
+        }
+        a2s[nb * 64 + lane] = (v4i){wd[0], wd[1], wd[2], wd[3]};       // k slab nb, byte r = channel 32nb + mfma_row(r,g)
+    }
+    __syncthreads();
+    {   // FC1 + GELU + quantize for hidden blocks wave, wave+NH, ...
+        v4i af[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) af[ks] = a2s[ks * 64 + lane];
+        const QDev qg = A.q_fc2in[branch];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int hb = wave + NH * i;
+            v16i acc;
+            const int* nc = A.f1_negcorr[branch] + hb * 32 + g * 4;
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                int4 t4 = *(const int4*)(nc + qd * 8);
+                acc[qd * 4 + 0] = t4.x; acc[qd * 4 + 1] = t4.y; acc[qd * 4 + 2] = t4.z; acc[qd * 4 + 3] = t4.w;
+            }
+            const v4i* wp = A.W1 + (size_t)hb * KS * 64 + lane;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) acc = mfma32(wp[ks * 64], af[ks], acc);
+            int wd[4];
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                const int n0 = hb * 32 + qd * 8 + g * 4;
+                const float4 m = *(const float4*)(A.f1_m[branch] + n0), bs = *(const float4*)(A.f1_bias[branch] + n0);
+                wd[qd] = pack4(quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 0], m.x, bs.x)), qg),
+                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 1], m.y, bs.y)), qg),
+                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 2], m.z, bs.z)), qg),
+                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 3], m.w, bs.w)), qg));
+                if (tap_ok) {
+                    if (A.tap_acc_fc1) *(int4*)(A.tap_acc_fc1 + canon * F + n0) = make_int4(acc[qd * 4], acc[qd * 4 + 1], acc[qd * 4 + 2], acc[qd * 4 + 3]);
+                    if (A.tap_g) *(int*)(A.tap_g + canon * F + n0) = wd[qd];
+                }
+            }
+            gs[hb * 64 + lane] = (v4i){wd[0], wd[1], wd[2], wd[3]};
+        }
+    }
+    __syncthreads();
+    {   // FC2 + second residual + scatter
+        v16i acc;
+        const int* nc = A.f2_negcorr[branch] + nb * 32 + g * 4;
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            int4 t4 = *(const int4*)(nc + qd * 8);
+            acc[qd * 4 + 0] = t4.x; acc[qd * 4 + 1] = t4.y; acc[qd * 4 + 2] = t4.z; acc[qd * 4 + 3] = t4.w;
+        }
+        const v4i* wp = A.W2 + (size_t)nb * HB * 64 + lane;
+#pragma unroll 4
+        for (int hb = 0; hb < HB; ++hb) acc = mfma32(wp[hb * 64], gs[hb * 64 + lane], acc);
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            const int n0 = nb * 32 + qd * 8 + g * 4;
+            const float4 m = *(const float4*)(A.f2_m[branch] + n0), bs = *(const float4*)(A.f2_bias[branch] + n0);
+            float4 o4 = make_float4(fmaf((float)acc[qd * 4 + 0], m.x, bs.x) + h[qd * 4 + 0], fmaf((float)acc[qd * 4 + 1], m.y, bs.y) + h[qd * 4 + 1],
+                                    fmaf((float)acc[qd * 4 + 2], m.z, bs.z) + h[qd * 4 + 2], fmaf((float)acc[qd * 4 + 3], m.w, bs.w) + h[qd * 4 + 3]);
+            if (pix >= 0) *(float4*)(A.y + (size_t)pix * C + n0) = o4;
+            if (tap_ok) {
+                if (A.tap_acc_fc2) *(int4*)(A.tap_acc_fc2 + canon * C + n0) = make_int4(acc[qd * 4], acc[qd * 4 + 1], acc[qd * 4 + 2], acc[qd * 4 + 3]);
+                if (A.tap_y) *(float4*)(A.tap_y + canon * C + n0) = o4;
             }
         }
     }
@@ -471,8 +822,9 @@ bool launch_score(const Geom& G, const float* x, int mode, float eps, const floa
 
 void launch_select(const double* scores, int B, int nW, int k_hi, int reverse, int* perm, hipStream_t st)
 {
-    size_t sh = (size_t)nW * 8 + (size_t)nW * 4 + 1024 * 4;
-    hipLaunchKernelGGL(select_kernel, dim3(B), dim3(1024), sh, st, scores, nW, k_hi, reverse, perm);
+    hipLaunchKernelGGL(select_rank_kernel, dim3((nW + 255) / 256, B), dim3(256), (size_t)nW * 8, st, scores, nW, k_hi,
+                       reverse, perm);
+    hipLaunchKernelGGL(select_place_kernel, dim3(B), dim3(1024), (size_t)nW * 4 + 4096, st, nW, k_hi, perm);
 }
 
 bool launch_ln_quant(const Geom& G, const LnArgs& A, bool gather, hipStream_t st)
@@ -509,6 +861,30 @@ void launch_gemm(const Geom& G, const GemmArgs& A, int epi, hipStream_t st)
         case EPI_PROJ: launch_gemm_e<EPI_PROJ>(G, A, st); break;
         case EPI_FC1: launch_gemm_e<EPI_FC1>(G, A, st); break;
         default: launch_gemm_e<EPI_FC2>(G, A, st); break;
+    }
+}
+
+bool fused_supported(int C, int mlp_ratio) { return (C == 96 || C == 128 || C == 192 || C == 256) && mlp_ratio == 4; }
+
+void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
+{
+    dim3 grid(G.B * G.nW);
+    switch (G.C / 32) {
+        case 3: hipLaunchKernelGGL((window_kernel<3>), grid, dim3(192), 0, st, G, A); break;
+        case 4: hipLaunchKernelGGL((window_kernel<4>), grid, dim3(256), 0, st, G, A); break;
+        case 6: hipLaunchKernelGGL((window_kernel<6>), grid, dim3(384), 0, st, G, A); break;
+        default: hipLaunchKernelGGL((window_kernel<8>), grid, dim3(512), 0, st, G, A); break;
+    }
+}
+
+void launch_token(const Geom& G, const TokArgs& A, hipStream_t st)
+{
+    dim3 grid(G.rows_total / 32);
+    switch (G.C / 32) {
+        case 3: hipLaunchKernelGGL((token_kernel<3>), grid, dim3(192), 0, st, G, A); break;
+        case 4: hipLaunchKernelGGL((token_kernel<4>), grid, dim3(256), 0, st, G, A); break;
+        case 6: hipLaunchKernelGGL((token_kernel<6>), grid, dim3(384), 0, st, G, A); break;
+        default: hipLaunchKernelGGL((token_kernel<8>), grid, dim3(512), 0, st, G, A); break;
     }
 }
 

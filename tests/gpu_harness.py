@@ -14,11 +14,13 @@ FLOAT_TAPS = ("h", "y_win")
 class GpuBlock:
     """A created block plus its workspace, destroyed on exit."""
 
-    def __init__(self, inp, shift=None):
+    def __init__(self, inp, shift=None, fused=None):
         self.spec = inp.spec
         self.desc = M.make_desc(inp.spec, shift)
         self.shared, self.branches = M.to_device(inp)
         self.blk = M.mixaq_block_create(self.desc, self.shared, self.branches)
+        if fused is not None:
+            M.mixaq_block_set_fused(self.blk, fused)
         self.ws = M.alloc_workspace(self.blk)
 
     def close(self):
@@ -49,13 +51,13 @@ class GpuBlock:
         return y
 
 
-def compare_block(inp, x_np, k_high, shift=None, perm_np=None, taps="all", label=""):
+def compare_block(inp, x_np, k_high, shift=None, perm_np=None, taps="all", fused=None):
     """Oracle vs GPU on one block: returns a dict of mismatch counts / errors; asserts nothing."""
     spec = inp.spec
     dev = torch.device("cuda:0")
     x = torch.from_numpy(x_np).to(dev)
     res = {}
-    with GpuBlock(inp, shift) as gb:
+    with GpuBlock(inp, shift, fused) as gb:
         g_scores, g_perm = gb.score_select(x, k_high)
         o_scores = O.score_windows(inp, x_np, shift)
         o_perm = O.select_windows(o_scores, k_high)

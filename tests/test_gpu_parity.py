@@ -33,21 +33,26 @@ SMALL = [
 ]
 
 
+@pytest.mark.parametrize("fused", [True, False])
 @pytest.mark.parametrize("B,H,W,C,heads,shift,keep,seed,kw", SMALL)
-def test_block_matches_oracle(B, H, W, C, heads, shift, keep, seed, kw):
+def test_block_matches_oracle(B, H, W, C, heads, shift, keep, seed, kw, fused):
+    """fused: the window + token kernels (C <= 256); otherwise the seven-kernel path."""
+    if fused and C > 256:
+        pytest.skip("the fused kernels cover C <= 256")
     spec, inp, x, k = _case(B, H, W, C, heads, shift, keep, seed, **kw)
-    print("case", B, H, W, C, heads, shift, keep, seed, kw, flush=True)
-    res = gh.compare_block(inp, x, k)
+    print("case", B, H, W, C, heads, shift, keep, seed, kw, "fused", fused, flush=True)
+    res = gh.compare_block(inp, x, k, fused=fused)
     print(res, flush=True)
     gh.assert_parity(res)
 
 
+@pytest.mark.parametrize("fused", [True, False])
 @pytest.mark.parametrize("shift", [0, 3])
-def test_config2_full_size(shift):
+def test_config2_full_size(shift, fused):
     """Swin-T stage 1 at detection scale, the size the benchmark times."""
     spec, inp, x, k = _case(1, 200, 336, 96, 3, shift, 0.5, 1002, blobs=True)
-    print("config 2 shift", shift, flush=True)
-    res = gh.compare_block(inp, x, k)
+    print("config 2 shift", shift, "fused", fused, flush=True)
+    res = gh.compare_block(inp, x, k, fused=fused)
     print(res, flush=True)
     gh.assert_parity(res)
 
