@@ -55,6 +55,19 @@ def kernel_model(name, C, F, heads, n_windows):
     raise KeyError(name)
 
 
+def read_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed counter summary (profiles/), or None."""
+    path = os.path.join(ROOT, "profiles", "cfg2_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) >= 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel:
+                return int(float(parts[2]))
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -115,23 +128,25 @@ def main():
     acc = {n: 0.0 for n in names}
     launches = {n: 0 for n in names}
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    sel_ms = 0.0
+    REP = 4                      # launches between an event pair (amortises the events' own cost)
     for _ in range(args.steps):
         ev0.record()
-        M.mixaq_score_windows(blocks[0], x, scores)
+        for _r in range(REP):
+            M.mixaq_score_windows(blocks[0], x, scores)
         ev1.record()
         ev1.synchronize()
-        acc["score"] += ev0.elapsed_time(ev1)
+        acc["score"] += ev0.elapsed_time(ev1) / REP
         launches["score"] += 1
         ev0.record()
-        M.mixaq_select_windows(scores, spec.B, spec.nW, k_high, 0, perm)
+        for _r in range(REP):
+            M.mixaq_select_windows(scores, spec.B, spec.nW, k_high, 0, perm)
         ev1.record()
         ev1.synchronize()
-        acc["select"] += ev0.elapsed_time(ev1)
+        acc["select"] += ev0.elapsed_time(ev1) / REP
         launches["select"] += 1
         cur = x
         for i, blk in enumerate(blocks):
-            ms = M.mixaq_block_forward_profile(blk, cur, perm, k_high, bufs[i % 2], ws)
+            ms = M.mixaq_block_forward_profile(blk, cur, perm, k_high, bufs[i % 2], ws, repeats=4)
             cur = bufs[i % 2]
             for n, v in ms.items():
                 if v > 0:
@@ -155,7 +170,7 @@ def main():
     dom = max(per_step, key=per_step.get)
     kd = kernels[dom]
     roofline = dict(kernel=dom, bound=kd["bound"], achieved=kd["achieved"], peak=kd["peak"], unit=kd["unit"],
-                    frac=kd["frac"], traffic=None, avg_ms=kd["avg_ms"])
+                    frac=kd["frac"], traffic=read_traffic(dom), avg_ms=kd["avg_ms"])
 
     windows_per_step = n_win * len(blocks)
     ops_per_step = 2 * macs_per_window(C) * windows_per_step
@@ -187,6 +202,12 @@ def main():
                int_tops=round(int_tops, 3), pct_int8_mfma_peak=round(100 * int_tops / PEAK_INT8_TOPS, 3),
                ms_per_block=round(ms_per_step / len(blocks), 5),
                roofline=roofline, kernels=kernels, cpu_baseline=cpu)
+    # a plain copy of known size, so that a counter run of this same command can calibrate
+    # FETCH_SIZE / WRITE_SIZE against bytes (64 MiB read + 64 MiB written)
+    calib_src = torch.empty(64 * 1024 * 1024, dtype=torch.uint8, device=dev)
+    calib_dst = torch.empty_like(calib_src)
+    calib_dst.copy_(calib_src)
+    torch.cuda.synchronize()
     print(json.dumps(out))
     for blk in blocks:
         M.mixaq_block_destroy(blk)

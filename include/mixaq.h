@@ -155,14 +155,15 @@ int mixaq_block_forward_taps(const mixaq_block *blk, const float *x, const int32
 int mixaq_block_set_fused(mixaq_block *blk, int32_t enable);
 
 /* Measurement aid for benchmarks (not part of the paper's method): one forward
- * call with a HIP event before every kernel launch on `stream`; synchronises the
- * stream and writes the duration of each kernel in milliseconds to the HOST array
- * kernel_ms[MIXAQ_NUM_KERNELS] (0 for kernels that did not run, e.g. score and
- * select when perm is given).  mixaq_kernel_name(i) names entry i. */
+ * call in which every kernel is launched `repeats` times in a row (each launch
+ * recomputes the same result) between two HIP events on `stream`; synchronises
+ * the stream and writes the mean duration of each kernel in milliseconds to the
+ * HOST array kernel_ms[MIXAQ_NUM_KERNELS] (0 for kernels that did not run, e.g.
+ * score and select when perm is given).  mixaq_kernel_name(i) names entry i. */
 #define MIXAQ_NUM_KERNELS 11
 int mixaq_block_forward_profile(const mixaq_block *blk, const float *x, const int32_t *perm, int32_t k_high,
                                 float *y, void *workspace, size_t workspace_bytes, void *stream,
-                                float *kernel_ms);
+                                int32_t repeats, float *kernel_ms);
 const char *mixaq_kernel_name(int32_t i);
 
 #ifdef __cplusplus

@@ -17,16 +17,21 @@
 #include <stdint.h>
 
 /* Uniform affine quantizer, x_hat = scale*(q - zero_point)  (Sec. 3.2: "step
- * sizes and zero points" per branch).  q = clamp(RNE(v*inv_s) + z) where the
- * product of the two binary32 numbers is taken exactly (it fits binary64) and
- * rounded half-to-even straight to an integer. */
+ * sizes and zero points" per branch).  q = clamp(round(v*inv_s + z)), rounding
+ * half-to-even, evaluated exactly: the product of two binary32 numbers fits
+ * binary64, and the integer zero point is added to its integer part so that no
+ * bit is lost before the rounding decision. */
 static inline int32_t orc_q(float v, float inv_s, int32_t z, int bits)
 {
-    double t = nearbyint((double)v * (double)inv_s) + (double)z;
-    double lo = -(double)(1 << (bits - 1)), hi = (double)((1 << (bits - 1)) - 1);
-    if (t < lo) t = lo;
-    if (t > hi) t = hi;
-    return (int32_t)t;
+    const double lo = -(double)(1 << (bits - 1)), hi = (double)((1 << (bits - 1)) - 1);
+    double p = (double)v * (double)inv_s;
+    if (!(fabs(p) < 1e9)) return p > 0 ? (int32_t)hi : (int32_t)lo;
+    double fl = floor(p), fr = p - fl;              /* exact, 0 <= fr < 1 */
+    double n = fl + (double)z;                      /* exact integer */
+    if (fr > 0.5 || (fr == 0.5 && fmod(n, 2.0) != 0.0)) n += 1.0;
+    if (n < lo) n = lo;
+    if (n > hi) n = hi;
+    return (int32_t)n;
 }
 
 /* 2^y for y <= 0: clamp at -100, split into integer and fraction in [-1/2,1/2],

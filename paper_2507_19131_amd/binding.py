@@ -11,7 +11,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libmixaq.so")
+# MIXAQ_LIBRARY lets a developer point at another build of the same library
+_LIB_PATH = os.environ.get("MIXAQ_LIBRARY") or os.path.join(_HERE, "libmixaq.so")
 _lib = None
 
 TOK = 49
@@ -72,7 +73,7 @@ def load():
         L.mixaq_block_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                           C.c_size_t, C.c_void_p]
         L.mixaq_block_forward_taps.argtypes = L.mixaq_block_forward.argtypes + [C.c_void_p]
-        L.mixaq_block_forward_profile.argtypes = L.mixaq_block_forward.argtypes + [C.POINTER(C.c_float)]
+        L.mixaq_block_forward_profile.argtypes = L.mixaq_block_forward.argtypes + [C.c_int32, C.POINTER(C.c_float)]
         L.mixaq_block_set_fused.argtypes = [C.c_void_p, C.c_int32]
         L.mixaq_kernel_name.restype = C.c_char_p
         L.mixaq_kernel_name.argtypes = [C.c_int32]
@@ -178,11 +179,12 @@ def mixaq_kernel_name(i):
     return load().mixaq_kernel_name(i).decode()
 
 
-def mixaq_block_forward_profile(blk, x, perm, k_high, y, workspace, stream=None):
-    """One forward with HIP events around every kernel; returns {kernel name: milliseconds}."""
+def mixaq_block_forward_profile(blk, x, perm, k_high, y, workspace, repeats=1, stream=None):
+    """One forward with HIP events around every kernel (each launched `repeats` times);
+    returns {kernel name: mean milliseconds}."""
     ms = (C.c_float * NUM_KERNELS)()
     _check(load().mixaq_block_forward_profile(blk, _ptr(x), _ptr(perm), k_high, _ptr(y), _ptr(workspace),
-                                              workspace.numel() * workspace.element_size(), _stream(stream), ms))
+                                              workspace.numel() * workspace.element_size(), _stream(stream), int(repeats), ms))
     return {mixaq_kernel_name(i): float(ms[i]) for i in range(NUM_KERNELS)}
 
 

@@ -65,9 +65,9 @@ QDev make_qdev(mixaq_qparam p, int bits)
     q.scale = p.scale;
     q.zp = p.zero_point;
     q.inv_s = 1.0f / p.scale;
-    q.lo = RND_MAGIC + (float)(qmin - p.zero_point);
-    q.hi = RND_MAGIC + (float)(qmax - p.zero_point);
-    q.off = p.zero_point - RND_MAGIC_BITS;
+    q.magic = RND_MAGIC + (float)p.zero_point;
+    q.lo = RND_MAGIC + (float)qmin;
+    q.hi = RND_MAGIC + (float)qmax;
     return q;
 }
 
@@ -234,6 +234,7 @@ struct Prof {
     hipEvent_t ev[MIXAQ_NUM_KERNELS + 1];
     int idx[MIXAQ_NUM_KERNELS + 1];
     int n = 0;
+    int repeats = 1;          // every kernel is launched this many times between its two events
 };
 
 int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, float* y, void* workspace,
@@ -259,14 +260,15 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, in
     static const mixaq_taps no_taps = {};
     const mixaq_taps& tp = taps ? *taps : no_taps;
 
+    const int reps = prof ? prof->repeats : 1;
     auto mark = [&](int kernel) {
         if (prof) { prof->idx[prof->n] = kernel; (void)hipEventRecord(prof->ev[prof->n++], st); }
     };
     if (!perm) {     // score and select here (single-block use)
         mark(0);
-        launch_score(G, x, d.score_mode, d.ln_eps, blk->score_gamma, blk->score_beta, ws.scores, st);
+        for (int r = 0; r < reps; ++r) launch_score(G, x, d.score_mode, d.ln_eps, blk->score_gamma, blk->score_beta, ws.scores, st);
         mark(1);
-        launch_select(ws.scores, d.B, blk->nW, k_high, 0, ws.perm, st);
+        for (int r = 0; r < reps; ++r) launch_select(ws.scores, d.B, blk->nW, k_high, 0, ws.perm, st);
         perm = ws.perm;
     }
     if (blk->fused) {
@@ -291,10 +293,12 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, in
         wa.tap_o = tp.acc_o; wa.tap_code = tp.a_proj_in;
         ta.tap_acc_proj = tp.acc_proj; ta.tap_h = tp.h; ta.tap_a2 = tp.a_fc1_in; ta.tap_acc_fc1 = tp.acc_fc1;
         ta.tap_g = tp.a_fc2_in; ta.tap_acc_fc2 = tp.acc_fc2; ta.tap_y = tp.y_win;
+        wa.poly = ta.poly = pinned_coefficients();
+        wa.taps = ta.taps = taps != nullptr;
         mark(9);
-        launch_window(G, wa, st);
+        for (int r = 0; r < reps; ++r) launch_window(G, wa, st);
         mark(10);
-        launch_token(G, ta, st);
+        for (int r = 0; r < reps; ++r) launch_token(G, ta, st);
         mark(-1);
         HIP_TRY(hipGetLastError());
         return MIXAQ_OK;
@@ -305,47 +309,49 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, in
     la.tap = tp.a_qkv_in;
     for (int br = 0; br < 2; ++br) { la.gamma[br] = blk->ln_gamma[0][br]; la.beta[br] = blk->ln_beta[0][br]; la.q[br] = blk->q_in[br]; }
     mark(2);
-    launch_ln_quant(G, la, true, st);
+    for (int r = 0; r < reps; ++r) launch_ln_quant(G, la, true, st);
     // QKV projection
     auto fill = [&](GemmArgs& a, const Linear& L, const int8_t* act) {
         a = GemmArgs{};
         a.A = act; a.Wp = L.Wp; a.K = L.K; a.N = L.N;
         for (int br = 0; br < 2; ++br) { a.m[br] = L.m[br]; a.bias[br] = L.bias[br]; a.negcorr[br] = L.negcorr[br]; }
         a.row_pix = ws.row_pix; a.row_canon = ws.row_canon;
+        a.poly = pinned_coefficients();
     };
     GemmArgs ga;
     fill(ga, blk->qkv, ws.a1);
     for (int br = 0; br < 2; ++br) for (int k = 0; k < 3; ++k) ga.q[br][k] = blk->q_qkv[br][k];
     ga.out8 = ws.qkv; ga.tap_acc = tp.acc_qkv; ga.tap_code = tp.qkv;
     mark(3);
-    launch_gemm(G, ga, EPI_QKV, st);
+    for (int r = 0; r < reps; ++r) launch_gemm(G, ga, EPI_QKV, st);
     // windowed attention
     AttnArgs aa = {};
     aa.qkv = ws.qkv; aa.perm = perm; aa.bias2 = blk->bias2; aa.out = ws.ao;
     for (int br = 0; br < 2; ++br) { aa.m2[br] = blk->m2[br]; aa.m_o[br] = blk->m_o[br]; aa.qp[br] = blk->q_p[br]; aa.qo[br] = blk->q_ao[br]; }
+    aa.poly = pinned_coefficients();
     aa.tap_s = tp.acc_s; aa.tap_p = tp.p; aa.tap_o = tp.acc_o; aa.tap_code = tp.a_proj_in;
     mark(4);
-    launch_attn(G, aa, st);
+    for (int r = 0; r < reps; ++r) launch_attn(G, aa, st);
     // output projection + first residual
     fill(ga, blk->proj, ws.ao);
     ga.outf = ws.h; ga.x = x; ga.tap_acc = tp.acc_proj; ga.tap_f = tp.h;
     mark(5);
-    launch_gemm(G, ga, EPI_PROJ, st);
+    for (int r = 0; r < reps; ++r) launch_gemm(G, ga, EPI_PROJ, st);
     // LN2 + quantize
     la.perm = nullptr; la.src = ws.h; la.out = ws.a2; la.tap = tp.a_fc1_in;
     for (int br = 0; br < 2; ++br) { la.gamma[br] = blk->ln_gamma[1][br]; la.beta[br] = blk->ln_beta[1][br]; la.q[br] = blk->q_fc1in[br]; }
     mark(6);
-    launch_ln_quant(G, la, false, st);
+    for (int r = 0; r < reps; ++r) launch_ln_quant(G, la, false, st);
     // FFN
     fill(ga, blk->fc1, ws.a2);
     for (int br = 0; br < 2; ++br) ga.q[br][0] = blk->q_fc2in[br];
     ga.out8 = ws.g; ga.tap_acc = tp.acc_fc1; ga.tap_code = tp.a_fc2_in;
     mark(7);
-    launch_gemm(G, ga, EPI_FC1, st);
+    for (int r = 0; r < reps; ++r) launch_gemm(G, ga, EPI_FC1, st);
     fill(ga, blk->fc2, ws.g);
     ga.resid = ws.h; ga.y = y; ga.tap_acc = tp.acc_fc2; ga.tap_f = tp.y_win;
     mark(8);
-    launch_gemm(G, ga, EPI_FC2, st);
+    for (int r = 0; r < reps; ++r) launch_gemm(G, ga, EPI_FC2, st);
     mark(-1);
     HIP_TRY(hipGetLastError());
     return MIXAQ_OK;
@@ -540,18 +546,19 @@ const char* mixaq_kernel_name(int32_t i)
 }
 
 int mixaq_block_forward_profile(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, float* y,
-                                void* workspace, size_t workspace_bytes, void* stream, float* kernel_ms)
+                                void* workspace, size_t workspace_bytes, void* stream, int32_t repeats, float* kernel_ms)
 {
     if (!kernel_ms) return fail(MIXAQ_E_NULL, "kernel_ms is NULL");
     Prof prof;
     for (int i = 0; i <= MIXAQ_NUM_KERNELS; ++i) HIP_TRY(hipEventCreate(&prof.ev[i]));
+    prof.repeats = repeats < 1 ? 1 : repeats;
     int rc = forward_impl(blk, x, perm, k_high, y, workspace, workspace_bytes, stream, nullptr, &prof);
     if (rc == MIXAQ_OK && hipStreamSynchronize((hipStream_t)stream) != hipSuccess) rc = fail(MIXAQ_E_HIP, "stream synchronisation failed");
     for (int i = 0; i < MIXAQ_NUM_KERNELS; ++i) kernel_ms[i] = 0.0f;
     if (rc == MIXAQ_OK)
         for (int i = 0; i + 1 < prof.n; ++i) {
             float ms = 0.0f;
-            if (hipEventElapsedTime(&ms, prof.ev[i], prof.ev[i + 1]) == hipSuccess) kernel_ms[prof.idx[i]] = ms;
+            if (hipEventElapsedTime(&ms, prof.ev[i], prof.ev[i + 1]) == hipSuccess) kernel_ms[prof.idx[i]] = ms / prof.repeats;
         }
     for (int i = 0; i <= MIXAQ_NUM_KERNELS; ++i) (void)hipEventDestroy(prof.ev[i]);
     return rc;

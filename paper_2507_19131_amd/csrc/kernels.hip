@@ -92,45 +92,58 @@ __global__ __launch_bounds__(256) void score_kernel(Geom G, const float* __restr
 // in the high group iff fewer than k_hi windows are ahead of it.  select_rank_kernel writes
 // that flag into perm; select_place_kernel (one workgroup per image) scans the flags and
 // overwrites perm with the high group then the low group, both in ascending index.
+// Rank: a wave ranks four windows at once, its lanes stride over the candidates held in LDS.
+constexpr int RANK_WPB = 16;                          // windows ranked per workgroup (4 per wave)
 __global__ __launch_bounds__(256) void select_rank_kernel(const double* __restrict__ scores, int nW, int k_hi, int reverse,
                                                           int* __restrict__ perm)
 {
-    extern __shared__ double sc[];                    // [nW]
-    const int b = blockIdx.y, w = blockIdx.x * 256 + threadIdx.x;
-    for (int i = threadIdx.x; i < nW; i += 256) sc[i] = scores[(size_t)b * nW + i];
+    extern __shared__ double rsc[];                   // all scores of the image
+    const int b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i = threadIdx.x; i < nW; i += 256) rsc[i] = scores[(size_t)b * nW + i];
     __syncthreads();
-    if (w >= nW) return;
-    const double sw = sc[w];
-    int rank = 0;
-    if (reverse) {
-        for (int v = 0; v < nW; ++v) { double sv = sc[v]; rank += (sv < sw || (sv == sw && v < w)) ? 1 : 0; }
-    } else {
-        for (int v = 0; v < nW; ++v) { double sv = sc[v]; rank += (sv > sw || (sv == sw && v < w)) ? 1 : 0; }
+    constexpr int Q = RANK_WPB / 4;                   // windows per wave, ranked together
+    const int w0 = blockIdx.x * RANK_WPB + wave * Q;
+    if (w0 >= nW) return;                             // whole wave, after the barrier
+    double sw[Q];
+    int rank[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) { sw[q] = rsc[min(w0 + q, nW - 1)]; rank[q] = 0; }
+    for (int v = lane; v < nW; v += 64) {
+        const double sv = rsc[v];
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const bool ahead = reverse ? (sv < sw[q]) : (sv > sw[q]);
+            rank[q] += (ahead || (sv == sw[q] && v < w0 + q)) ? 1 : 0;
+        }
     }
-    perm[(size_t)b * nW + w] = rank < k_hi ? 1 : 0;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) rank[q] += __shfl_xor(rank[q], o, 64);
+        if (lane == 0 && w0 + q < nW) perm[(size_t)b * nW + w0 + q] = rank[q] < k_hi ? 1 : 0;
+    }
 }
 
 __global__ __launch_bounds__(1024) void select_place_kernel(int nW, int k_hi, int* __restrict__ perm)
 {
     extern __shared__ int smi[];
     int* flag = smi;                                  // [nW]
-    int* wsum = smi + nW;                             // [1024]
-    const int b = blockIdx.x, tid = threadIdx.x;
+    int* wsum = smi + nW;                             // [16] per-wave totals
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int i = tid; i < nW; i += 1024) flag[i] = perm[(size_t)b * nW + i];
     __syncthreads();
     const int chunk = (nW + 1023) / 1024;
     const int lo = min(tid * chunk, nW), hi = min(lo + chunk, nW);
     int cnt = 0;
     for (int i = lo; i < hi; ++i) cnt += flag[i];
-    wsum[tid] = cnt;
+    int incl = cnt;                                   // inclusive scan inside the wave
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) { int t = __shfl_up(incl, o, 64); if (lane >= o) incl += t; }
+    if (lane == 63) wsum[wave] = incl;
     __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {
-        int add = tid >= o ? wsum[tid - o] : 0;
-        __syncthreads();
-        wsum[tid] += add;
-        __syncthreads();
-    }
-    int nh = wsum[tid] - cnt;                         // high windows before this chunk
+    int before = 0;
+    for (int k = 0; k < wave; ++k) before += wsum[k];
+    int nh = before + incl - cnt;                     // high windows before this chunk
     for (int i = lo; i < hi; ++i) {
         int nl = i - nh;                              // low windows before i
         if (flag[i]) perm[(size_t)b * nW + nh++] = i;
@@ -200,7 +213,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& A, const Geom& G, int b
         float f2 = fmaf((float)a2, m.z, bs.z), f3 = fmaf((float)a3, m.w, bs.w);
         if (A.tap_acc && canon >= 0) *(int4*)(A.tap_acc + (size_t)canon * N + n0) = make_int4(a0, a1, a2, a3);
         if (EPI == EPI_QKV || EPI == EPI_FC1) {
-            if (EPI == EPI_FC1) { f0 = gelu_pinned(f0); f1 = gelu_pinned(f1); f2 = gelu_pinned(f2); f3 = gelu_pinned(f3); }
+            if (EPI == EPI_FC1) { f0 = gelu_pinned(f0, A.poly); f1 = gelu_pinned(f1, A.poly); f2 = gelu_pinned(f2, A.poly); f3 = gelu_pinned(f3, A.poly); }
             const QDev& q = A.q[branch][EPI == EPI_QKV ? n0 / G.C : 0];
             int code = pack4(quant_code(f0, q), quant_code(f1, q), quant_code(f2, q), quant_code(f3, q));
             *(int*)(A.out8 + (size_t)row * N + n0) = code;
@@ -282,6 +295,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
 // mfma_row(r,g)][j], zero for keys >= 49.  Returns the raw P.V sums (lane = query, register
 // r = dim mfma_row(r,g)).
 struct AttnCore {
+    const PolyCoef* poly;
     const float* bm;          // [49 keys][64 queries] (bias + mask) * log2e of this head and mask type
     float m2;
     QDev qp;
@@ -289,6 +303,7 @@ struct AttnCore {
     int8_t* tap_p;
 };
 
+template <bool TAPS>
 __device__ __forceinline__ void attention_core(const v4i (&qf)[2], const v4i (&kf)[2], const v4i (&vt)[2],
                                                const AttnCore& A, int j, int g, v16i (&o)[2])
 {
@@ -326,7 +341,7 @@ __device__ __forceinline__ void attention_core(const v4i (&qf)[2], const v4i (&k
                 const int key = kb * 32 + (r >> 2) * 8 + (r & 3);
                 if (key < TOK) {
                     const int kk = key + g * 4;
-                    float e = kk < TOK ? exp2_pinned(lg[kb][r] - mx) : 0.0f;
+                    float e = kk < TOK ? exp2_pinned(lg[kb][r] - mx, *A.poly) : 0.0f;
                     lg[kb][r] = e;
                     den += (double)e;
                 }
@@ -347,7 +362,7 @@ __device__ __forceinline__ void attention_core(const v4i (&qf)[2], const v4i (&k
                         const int kk = key + g * 4;
                         if (kk < TOK) {
                             c[e] = quant_code(lg[kb][r] * rden, A.qp);
-                            if (qi < TOK) {
+                            if (TAPS && qi < TOK) {
                                 if (A.tap_s) A.tap_s[qi * TOK + kk] = s[kb][ib][r];
                                 if (A.tap_p) A.tap_p[qi * TOK + kk] = (int8_t)c[e];
                             }
@@ -368,6 +383,7 @@ __device__ __forceinline__ void attention_core(const v4i (&qf)[2], const v4i (&k
 
 // zero-point correction, dequantization and requantization of the P.V sums; writes the codes
 // of head `head` for the window's tokens to out[row0 + token][C] (and the taps).
+template <bool TAPS>
 __device__ __forceinline__ void attention_store(const v16i (&o)[2], const int* csum, const QDev& qp, const QDev& qo, float m_o,
                                                 int j, int g, int head, int C, int8_t* out, int row0, int32_t* tap_o,
                                                 int8_t* tap_code, size_t canon_row0)
@@ -387,8 +403,8 @@ __device__ __forceinline__ void attention_store(const v16i (&o)[2], const int* c
                 const int ch = head * HD + d0;
                 *(int*)(out + (size_t)(row0 + qi) * C + ch) = code;
                 size_t ci = (canon_row0 + qi) * C + ch;
-                if (tap_o) *(int4*)(tap_o + ci) = make_int4(a0, a1, a2, a3);
-                if (tap_code) *(int*)(tap_code + ci) = code;
+                if (TAPS && tap_o) *(int4*)(tap_o + ci) = make_int4(a0, a1, a2, a3);
+                if (TAPS && tap_code) *(int*)(tap_code + ci) = code;
             }
         }
     }
@@ -446,14 +462,16 @@ __global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
         for (int qd = 0; qd < 4; ++qd) {
             int c[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { c[e] = vs[wave][(kb * 32 + qd * 8 + g * 4 + e) * HD + j]; cs += c[e]; }
+            for (int e = 0; e < 4; ++e) c[e] = vs[wave][(kb * 32 + qd * 8 + g * 4 + e) * HD + j];
             wd[qd] = pack4(c[0], c[1], c[2], c[3]);
+            cs = __builtin_amdgcn_sdot4(wd[qd], 0x01010101, cs, false);
         }
         vt[kb] = (v4i){wd[0], wd[1], wd[2], wd[3]};
     }
     cs += __shfl_xor(cs, 32, 64);
     if (g == 0) csum[wave][j] = cs;
     AttnCore core;
+    core.poly = &A.poly;
     core.bm = A.bias2 + ((size_t)(mtype * G.heads + head) * TOK) * 64;
     core.m2 = A.m2[branch];
     core.qp = A.qp[branch];
@@ -461,10 +479,10 @@ __global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
     core.tap_s = A.tap_s ? A.tap_s + tb : nullptr;
     core.tap_p = A.tap_p ? A.tap_p + tb : nullptr;
     v16i o[2];
-    attention_core(qf, kf, vt, core, j, g, o);
+    attention_core<true>(qf, kf, vt, core, j, g, o);
     __builtin_amdgcn_s_waitcnt(0);
     __builtin_amdgcn_wave_barrier();
-    attention_store(o, csum[wave], core.qp, A.qo[branch], A.m_o[branch], j, g, head, G.C, A.out, row0, A.tap_o, A.tap_code,
+    attention_store<true>(o, csum[wave], core.qp, A.qo[branch], A.m_o[branch], j, g, head, G.C, A.out, row0, A.tap_o, A.tap_code,
                     (size_t)canon_slot * TOK);
 }
 
@@ -473,14 +491,17 @@ __global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
 //   gather (shift folded into the index map) + LN1 + quantize, shared through LDS as MFMA
 //   fragments -> per head: q, k (transposed product, lane = token) and v (plain product, lane =
 //   dim) straight into operand registers -> attention core -> codes of the attention output.
+#ifndef WIN_WAVES_PER_EU
+#define WIN_WAVES_PER_EU 3
+#endif
 template <int NH>
 struct WinCfg {
     static constexpr int LPT = NH == 3 ? 2 : (NH == 8 ? 8 : 4);     // lanes per token in the LN phase (49 tokens fit one pass)
     static constexpr int NV = NH * 32 / (4 * LPT);
 };
 
-template <int NH>
-__global__ __launch_bounds__(NH * 64) void window_kernel(Geom G, WinArgs A)
+template <int NH, bool TAPS>
+__global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAVES_PER_EU))) void window_kernel(Geom G, WinArgs A)
 {
     constexpr int C = NH * 32, KS = NH, LPT = WinCfg<NH>::LPT, NV = WinCfg<NH>::NV, NT = NH * 64;
     static_assert(NT / LPT >= TOK, "one pass must cover the window");
@@ -520,11 +541,14 @@ __global__ __launch_bounds__(NH * 64) void window_kernel(Geom G, WinArgs A)
                 const int ch = (k * LPT + sub) * 4;
                 int code = pack4(quant_code(v[k].x, q), quant_code(v[k].y, q), quant_code(v[k].z, q), quant_code(v[k].w, q));
                 a1w[frag_dw(t, ch)] = code;
-                if (A.tap_a1) *(int*)(A.tap_a1 + (size_t)canon * C + ch) = code;
+                if (TAPS && A.tap_a1) *(int*)(A.tap_a1 + (size_t)canon * C + ch) = code;
             }
         }
     }
     __syncthreads();
+#ifdef MIXAQ_PRIO
+    __builtin_amdgcn_s_setprio(1);
+#endif
     const int head = wave;
     v4i bf[2][KS];
 #pragma unroll
@@ -561,7 +585,7 @@ __global__ __launch_bounds__(NH * 64) void window_kernel(Geom G, WinArgs A)
                 const int a0 = acc[qd * 4 + 0], a1 = acc[qd * 4 + 1], a2 = acc[qd * 4 + 2], a3 = acc[qd * 4 + 3];
                 wd[qd] = pack4(quant_code(fmaf((float)a0, m.x, bs.x), qq), quant_code(fmaf((float)a1, m.y, bs.y), qq),
                                quant_code(fmaf((float)a2, m.z, bs.z), qq), quant_code(fmaf((float)a3, m.w, bs.w), qq));
-                if (tok < TOK) {
+                if (TAPS && tok < TOK) {
                     if (A.tap_acc) *(int4*)(A.tap_acc + (canon_row0 + tok) * (3 * C) + n0) = make_int4(a0, a1, a2, a3);
                     if (A.tap_qkv) *(int*)(A.tap_qkv + (canon_row0 + tok) * (3 * C) + n0) = wd[qd];
                 }
@@ -598,20 +622,24 @@ __global__ __launch_bounds__(NH * 64) void window_kernel(Geom G, WinArgs A)
                     if (tb * 32 + qd * 8 + e < TOK) {
                         if (tok < TOK) {
                             c[e] = quant_code(fmaf((float)acc[qd * 4 + e], m, bs), qv);
-                            if (A.tap_acc) A.tap_acc[(canon_row0 + tok) * (3 * C) + n] = acc[qd * 4 + e];
-                            if (A.tap_qkv) A.tap_qkv[(canon_row0 + tok) * (3 * C) + n] = (int8_t)c[e];
+                            if (TAPS && A.tap_acc) A.tap_acc[(canon_row0 + tok) * (3 * C) + n] = acc[qd * 4 + e];
+                            if (TAPS && A.tap_qkv) A.tap_qkv[(canon_row0 + tok) * (3 * C) + n] = (int8_t)c[e];
                         }
                     }
-                    cs += c[e];
                 }
                 wd[qd] = pack4(c[0], c[1], c[2], c[3]);
+                cs = __builtin_amdgcn_sdot4(wd[qd], 0x01010101, cs, false);
             }
             vt[tb] = (v4i){wd[0], wd[1], wd[2], wd[3]};
         }
         cs += __shfl_xor(cs, 32, 64);
         if (g == 0) csum[wave][j] = cs;
     }
+#ifdef MIXAQ_PRIO
+    __builtin_amdgcn_s_setprio(2);
+#endif
     AttnCore core;
+    core.poly = &A.poly;
     core.bm = A.bias2 + ((size_t)(mask_type(G, w) * NH + head) * TOK) * 64;
     core.m2 = A.m2[branch];
     core.qp = A.qp[branch];
@@ -619,10 +647,10 @@ __global__ __launch_bounds__(NH * 64) void window_kernel(Geom G, WinArgs A)
     core.tap_s = A.tap_s ? A.tap_s + tbase : nullptr;
     core.tap_p = A.tap_p ? A.tap_p + tbase : nullptr;
     v16i o[2];
-    attention_core(qk[0], qk[1], vt, core, j, g, o);
+    attention_core<TAPS>(qk[0], qk[1], vt, core, j, g, o);
     __builtin_amdgcn_s_waitcnt(0);
     __builtin_amdgcn_wave_barrier();
-    attention_store(o, csum[wave], core.qp, A.qo[branch], A.m_o[branch], j, g, head, C, A.out, row0, A.tap_o, A.tap_code, canon_row0);
+    attention_store<TAPS>(o, csum[wave], core.qp, A.qo[branch], A.m_o[branch], j, g, head, C, A.out, row0, A.tap_o, A.tap_code, canon_row0);
 }
 
 // ------------------------------------------------------------------ fused token kernel
@@ -630,8 +658,11 @@ __global__ __launch_bounds__(NH * 64) void window_kernel(Geom G, WinArgs A)
 //   proj + first residual (wave w owns channels 32w..32w+31, h stays in registers) -> LN2 with
 //   statistics exchanged through LDS -> quantize -> FC1 (each wave 4 hidden blocks) + GELU +
 //   quantize, codes to LDS as fragments -> FC2 + second residual -> scatter to the map.
-template <int NH>
-__global__ __launch_bounds__(NH * 64) void token_kernel(Geom G, TokArgs A)
+#ifndef TOK_WAVES_PER_EU
+#define TOK_WAVES_PER_EU 4
+#endif
+template <int NH, bool TAPS>
+__global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(TOK_WAVES_PER_EU))) void token_kernel(Geom G, TokArgs A)
 {
     constexpr int C = NH * 32, KS = NH, HB = 4 * NH, F = 4 * C;
     __shared__ v4i a2s[KS * 64];
@@ -643,7 +674,7 @@ __global__ __launch_bounds__(NH * 64) void token_kernel(Geom G, TokArgs A)
     const bool valid = branch ? (row - G.base_lo < G.rows_lo) : (row < G.rows_hi);
     const int pix = valid ? A.row_pix[row] : -1;
     const size_t canon = valid ? (size_t)A.row_canon[row] : 0;
-    const bool tap_ok = valid;
+    const bool tap_ok = TAPS && valid;
     const int nb = wave;
     float h[16];
     {   // output projection + first residual
@@ -715,6 +746,9 @@ __global__ __launch_bounds__(NH * 64) void token_kernel(Geom G, TokArgs A)
         a2s[nb * 64 + lane] = (v4i){wd[0], wd[1], wd[2], wd[3]};       // k slab nb, byte r = channel 32nb + mfma_row(r,g)
     }
     __syncthreads();
+#ifdef MIXAQ_PRIO
+    __builtin_amdgcn_s_setprio(1);
+#endif
     {   // FC1 + GELU + quantize for hidden blocks wave, wave+NH, ...
         v4i af[KS];
 #pragma unroll
@@ -738,18 +772,24 @@ __global__ __launch_bounds__(NH * 64) void token_kernel(Geom G, TokArgs A)
             for (int qd = 0; qd < 4; ++qd) {
                 const int n0 = hb * 32 + qd * 8 + g * 4;
                 const float4 m = *(const float4*)(A.f1_m[branch] + n0), bs = *(const float4*)(A.f1_bias[branch] + n0);
-                wd[qd] = pack4(quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 0], m.x, bs.x)), qg),
-                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 1], m.y, bs.y)), qg),
-                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 2], m.z, bs.z)), qg),
-                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 3], m.w, bs.w)), qg));
+                wd[qd] = pack4(quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 0], m.x, bs.x), A.poly), qg),
+                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 1], m.y, bs.y), A.poly), qg),
+                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 2], m.z, bs.z), A.poly), qg),
+                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 3], m.w, bs.w), A.poly), qg));
                 if (tap_ok) {
                     if (A.tap_acc_fc1) *(int4*)(A.tap_acc_fc1 + canon * F + n0) = make_int4(acc[qd * 4], acc[qd * 4 + 1], acc[qd * 4 + 2], acc[qd * 4 + 3]);
                     if (A.tap_g) *(int*)(A.tap_g + canon * F + n0) = wd[qd];
                 }
             }
             gs[hb * 64 + lane] = (v4i){wd[0], wd[1], wd[2], wd[3]};
+#ifdef MIXAQ_PRIO
+            if (i == 1) __builtin_amdgcn_s_setprio(2);
+#endif
         }
     }
+#ifdef MIXAQ_PRIO
+    __builtin_amdgcn_s_setprio(3);
+#endif
     __syncthreads();
     {   // FC2 + second residual + scatter
         v16i acc;
@@ -822,9 +862,9 @@ bool launch_score(const Geom& G, const float* x, int mode, float eps, const floa
 
 void launch_select(const double* scores, int B, int nW, int k_hi, int reverse, int* perm, hipStream_t st)
 {
-    hipLaunchKernelGGL(select_rank_kernel, dim3((nW + 255) / 256, B), dim3(256), (size_t)nW * 8, st, scores, nW, k_hi,
+    hipLaunchKernelGGL(select_rank_kernel, dim3((nW + RANK_WPB - 1) / RANK_WPB, B), dim3(256), (size_t)nW * 8, st, scores, nW, k_hi,
                        reverse, perm);
-    hipLaunchKernelGGL(select_place_kernel, dim3(B), dim3(1024), (size_t)nW * 4 + 4096, st, nW, k_hi, perm);
+    hipLaunchKernelGGL(select_place_kernel, dim3(B), dim3(1024), (size_t)nW * 4 + 64, st, nW, k_hi, perm);
 }
 
 bool launch_ln_quant(const Geom& G, const LnArgs& A, bool gather, hipStream_t st)
@@ -869,23 +909,33 @@ bool fused_supported(int C, int mlp_ratio) { return (C == 96 || C == 128 || C ==
 void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
 {
     dim3 grid(G.B * G.nW);
+#define WIN_CASE(NH)                                                                                     \
+    if (A.taps) hipLaunchKernelGGL((window_kernel<NH, true>), grid, dim3(NH * 64), 0, st, G, A);        \
+    else hipLaunchKernelGGL((window_kernel<NH, false>), grid, dim3(NH * 64), 0, st, G, A);              \
+    break
     switch (G.C / 32) {
-        case 3: hipLaunchKernelGGL((window_kernel<3>), grid, dim3(192), 0, st, G, A); break;
-        case 4: hipLaunchKernelGGL((window_kernel<4>), grid, dim3(256), 0, st, G, A); break;
-        case 6: hipLaunchKernelGGL((window_kernel<6>), grid, dim3(384), 0, st, G, A); break;
-        default: hipLaunchKernelGGL((window_kernel<8>), grid, dim3(512), 0, st, G, A); break;
+        case 3: WIN_CASE(3);
+        case 4: WIN_CASE(4);
+        case 6: WIN_CASE(6);
+        default: WIN_CASE(8);
     }
+#undef WIN_CASE
 }
 
 void launch_token(const Geom& G, const TokArgs& A, hipStream_t st)
 {
     dim3 grid(G.rows_total / 32);
+#define TOK_CASE(NH)                                                                                     \
+    if (A.taps) hipLaunchKernelGGL((token_kernel<NH, true>), grid, dim3(NH * 64), 0, st, G, A);         \
+    else hipLaunchKernelGGL((token_kernel<NH, false>), grid, dim3(NH * 64), 0, st, G, A);               \
+    break
     switch (G.C / 32) {
-        case 3: hipLaunchKernelGGL((token_kernel<3>), grid, dim3(192), 0, st, G, A); break;
-        case 4: hipLaunchKernelGGL((token_kernel<4>), grid, dim3(256), 0, st, G, A); break;
-        case 6: hipLaunchKernelGGL((token_kernel<6>), grid, dim3(384), 0, st, G, A); break;
-        default: hipLaunchKernelGGL((token_kernel<8>), grid, dim3(512), 0, st, G, A); break;
+        case 3: TOK_CASE(3);
+        case 4: TOK_CASE(4);
+        case 6: TOK_CASE(6);
+        default: TOK_CASE(8);
     }
+#undef TOK_CASE
 }
 
 void launch_attn(const Geom& G, const AttnArgs& A, hipStream_t st)

@@ -17,27 +17,29 @@ constexpr int ROW_TILE = 64;     // rows per GEMM tile; branch regions are padde
 constexpr float LOG2E_F = 0x1.715476p+0f;
 constexpr float MASK_VALUE = -100.0f;
 constexpr float RND_MAGIC = 12582912.0f;          // 1.5 * 2^23: adding it rounds to an integer, ties to even
-constexpr int RND_MAGIC_BITS = 0x4B400000;
 
-// One activation quantizer prepared for the device.  code = clamp(rne(v*inv_s) + zp):
-// u = fma(v, inv_s, MAGIC) rounds the exact product half-to-even, the clamp is taken
-// on u, and the integer is the low mantissa of u.
+// One activation quantizer prepared for the device.  code = clamp(round-half-even(v*inv_s + zp)):
+// u = fma(v, inv_s, MAGIC + zp) rounds the exact sum to an integer in one operation (ties to the
+// even code), the clamp is taken on u, and the code is the low mantissa byte of u.
 struct QDev {
     float inv_s;      // 1.0f / scale
-    float lo, hi;     // MAGIC + (qmin - zp), MAGIC + (qmax - zp)
-    int   off;        // zp - RND_MAGIC_BITS
+    float magic;      // MAGIC + zp
+    float lo, hi;     // MAGIC + qmin, MAGIC + qmax
     float scale;
     int   zp;
 };
 
+// returns the bit pattern of u; its low byte is the int8 code
 __device__ __forceinline__ int quant_code(float v, const QDev& q)
 {
-    float u = fmaf(v, q.inv_s, RND_MAGIC);
+    float u = fmaf(v, q.inv_s, q.magic);
     u = __builtin_amdgcn_fmed3f(u, q.lo, q.hi);
-    return __float_as_int(u) + q.off;
+    return __float_as_int(u);
 }
+// the code as a sign-extended integer
+__device__ __forceinline__ int code_value(int ubits) { return (int)(int8_t)(ubits & 0xff); }
 
-// four int codes -> one dword of int8 (byte k = code k)
+// low bytes of four words -> one dword of int8 (byte k = code k)
 __device__ __forceinline__ int pack4(int c0, int c1, int c2, int c3)
 {
     int lo = __builtin_amdgcn_perm(c1, c0, 0x0c0c0400);
@@ -45,42 +47,38 @@ __device__ __forceinline__ int pack4(int c0, int c1, int c2, int c3)
     return lo | hi;
 }
 
+// Coefficients of the two pinned polynomials.  They travel as kernel arguments so that they sit
+// in scalar registers and every Horner step is one v_fma with a scalar addend.
+struct PolyCoef {
+    float e[6];       // 2^r on [-1/2, 1/2], degree 5, e[0] = constant term
+    float g[15];      // a*Phi(-a) in t = 2a/5.5 - 1, degree 14, g[0] = constant term
+    float gscale;     // 2/5.5
+};
+
 // 2^y for y <= 0 (clamped at -100): split, degree-5 polynomial, exact scaling.
-__device__ __forceinline__ float exp2_pinned(float y)
+__device__ __forceinline__ float exp2_pinned(float y, const PolyCoef& P)
 {
     y = fmaxf(y, -100.0f);
     float n = rintf(y);
     float r = y - n;
-    float p = 0x1.5f48c8p-10f;
-    p = fmaf(p, r, 0x1.3d107cp-7f);
-    p = fmaf(p, r, 0x1.c6aeccp-5f);
-    p = fmaf(p, r, 0x1.ebf906p-3f);
-    p = fmaf(p, r, 0x1.62e430p-1f);
-    p = fmaf(p, r, 0x1.000002p+0f);
+    float p = P.e[5];
+    p = fmaf(p, r, P.e[4]);
+    p = fmaf(p, r, P.e[3]);
+    p = fmaf(p, r, P.e[2]);
+    p = fmaf(p, r, P.e[1]);
+    p = fmaf(p, r, P.e[0]);
     return ldexpf(p, (int)n);
 }
 
 // GELU(x) = max(x,0) - a*Phi(-a), a = |x|; the remainder is a degree-14 polynomial
 // in t = 2a/5.5 - 1 for a <= 5.5 and constant beyond.
-__device__ __forceinline__ float gelu_pinned(float x)
+__device__ __forceinline__ float gelu_pinned(float x, const PolyCoef& P)
 {
     float a = fminf(fabsf(x), 5.5f);
-    float t = fmaf(a, 0x1.745d18p-2f, -1.0f);
-    float h = 0x1.280820p-5f;
-    h = fmaf(h, t, -0x1.42e9b8p-5f);
-    h = fmaf(h, t, -0x1.3d2fc0p-3f);
-    h = fmaf(h, t, 0x1.e1f934p-3f);
-    h = fmaf(h, t, 0x1.7cae60p-3f);
-    h = fmaf(h, t, -0x1.18547cp-1f);
-    h = fmaf(h, t, 0x1.88e9f6p-3f);
-    h = fmaf(h, t, 0x1.d7ab76p-2f);
-    h = fmaf(h, t, -0x1.46f9bap-1f);
-    h = fmaf(h, t, 0x1.0a7892p-2f);
-    h = fmaf(h, t, 0x1.711f2ap-3f);
-    h = fmaf(h, t, -0x1.3c122ap-2f);
-    h = fmaf(h, t, 0x1.8794f2p-3f);
-    h = fmaf(h, t, -0x1.f0423cp-5f);
-    h = fmaf(h, t, 0x1.0c8760p-7f);
+    float t = fmaf(a, P.gscale, -1.0f);
+    float h = P.g[14];
+#pragma unroll
+    for (int k = 13; k >= 0; --k) h = fmaf(h, t, P.g[k]);
     return fmaxf(x, 0.0f) - h;
 }
 

@@ -50,11 +50,11 @@ def test_gelu_pinned_against_erf_form():
 def _q_exact(v, scale, z, bits):
     """Exact rational evaluation of the quantizer definition."""
     inv = np.float32(1.0) / np.float32(scale)
-    t = Fraction(float(np.float32(v))) * Fraction(float(inv))
+    t = Fraction(float(np.float32(v))) * Fraction(float(inv)) + z
     fl = t.numerator // t.denominator
     fr = t - fl
     n = fl + 1 if fr > Fraction(1, 2) else fl if fr < Fraction(1, 2) else (fl if fl % 2 == 0 else fl + 1)
-    return int(min(max(n + z, -(1 << (bits - 1))), (1 << (bits - 1)) - 1))
+    return int(min(max(n, -(1 << (bits - 1))), (1 << (bits - 1)) - 1))
 
 
 @pytest.mark.parametrize("bits", [2, 4, 8])
@@ -80,7 +80,8 @@ def test_quantizer_roundtrip_and_exact_rounding(bits):
     s = 2.0 ** -6
     assert L.orc_quantize(0.5 * s, s, 0, 8) == 0 and L.orc_quantize(1.5 * s, s, 0, 8) == 2
     assert L.orc_quantize(2.5 * s, s, 0, 8) == 2 and L.orc_quantize(-0.5 * s, s, 0, 8) == 0
-    assert L.orc_quantize(2.5 * s, s, 1, 8) == 3       # the zero point is added after rounding
+    assert L.orc_quantize(2.5 * s, s, 1, 8) == 4       # the zero point is inside the rounding: 3.5 -> 4
+    assert L.orc_quantize(1.5 * s, s, 1, 8) == 2 and L.orc_quantize(-1.5 * s, s, 3, 8) == 2
 
 
 def test_layernorm_against_numpy():
