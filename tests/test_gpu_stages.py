@@ -1,0 +1,79 @@
+"""GPU parity on whole stages of the benchmark workloads: blocks chained on one map, the score
+taken once on the stage input and shared by the stage's blocks, one keep ratio per block pair."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_19131_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import gpu_harness as gh
+    import oracle_api as O
+    from paper_2507_19131_amd import binding as M
+
+
+def run_stage(spec, shifts, keep, seed, blobs, outliers, ranges):
+    """Returns (y_gpu, y_oracle, perm_gpu, perm_oracle) after the chain of blocks."""
+    dev = torch.device("cuda:0")
+    x_np = synth.make_feature_map(spec, seed, blobs=blobs, outlier_channels=outliers)
+    inputs = [synth.make_block_inputs(spec, seed + 10 * i, ranges=ranges) for i in range(len(shifts))]
+    k = synth.keep_count(spec.nW, keep)
+    x = torch.from_numpy(x_np).to(dev)
+    blocks = [gh.GpuBlock(inp, shift) for inp, shift in zip(inputs, shifts)]
+    try:
+        _, perm = blocks[0].score_select(x, k)
+        cur = x
+        for gb in blocks:
+            cur = gb.forward(cur, perm, k)
+        torch.cuda.synchronize()
+        y_gpu, perm_gpu = cur.cpu().numpy(), perm.cpu().numpy()
+    finally:
+        for gb in blocks:
+            gb.close()
+    perm_o = O.select_windows(O.score_windows(inputs[0], x_np), k)
+    cur = x_np
+    for inp, shift in zip(inputs, shifts):
+        cur, _ = O.block_forward(inp, cur, perm_o, k, shift, threads=16)
+    return y_gpu, cur, perm_gpu, perm_o
+
+
+def check(y_gpu, y_or, perm_gpu, perm_or):
+    assert np.array_equal(perm_gpu, perm_or)
+    assert not np.isnan(y_gpu).any()
+    rms = float(np.sqrt(np.mean(y_or.astype(np.float64) ** 2)))
+    err = float(np.max(np.abs(y_gpu.astype(np.float64) - y_or)))
+    print("max abs err", err, "rms", rms, "bit identical", np.array_equal(y_gpu, y_or), flush=True)
+    assert err <= 1e-3 * rms
+
+
+def test_config2_stage_pair():
+    wl = synth.workload("cfg2")
+    st = wl["stages"][0]
+    check(*run_stage(st["spec"], st["shifts"], wl["keep"][0], wl["seed"], wl["blobs"], wl["outliers"], wl.get("ranges")))
+
+
+@pytest.mark.parametrize("keep", [0.25, 0.5, 0.75])
+def test_config3_six_blocks(keep):
+    wl = synth.workload("cfg3")
+    st = wl["stages"][0]
+    print("config 3 keep", keep, flush=True)
+    check(*run_stage(st["spec"], st["shifts"], keep, wl["seed"], wl["blobs"], wl["outliers"], wl.get("ranges")))
+
+
+@pytest.mark.parametrize("stage", [0, 1, 2, 3])
+def test_config4_stage_shapes(stage):
+    """W4A4 with 2-bit low windows; every stage of Swin-T at 800x1344 on its own synthetic map."""
+    wl = synth.workload("cfg4")
+    st = wl["stages"][stage]
+    print("config 4 stage", stage, flush=True)
+    check(*run_stage(st["spec"], st["shifts"], wl["keep"][0], wl["seed"] + stage, wl["blobs"], wl["outliers"], wl.get("ranges")))
+
+
+@pytest.mark.parametrize("stage", [0, 1])
+def test_config5_swin_b_stages(stage):
+    wl = synth.workload("cfg5")
+    st = wl["stages"][stage]
+    print("config 5 stage", stage, flush=True)
+    check(*run_stage(st["spec"], st["shifts"], wl["keep"][0], wl["seed"] + stage, wl["blobs"], wl["outliers"], wl.get("ranges")))
