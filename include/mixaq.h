@@ -135,6 +135,12 @@ int mixaq_score_windows(const mixaq_block *blk, const float *x, double *scores, 
 int mixaq_select_windows(const double *scores, int32_t B, int32_t nW, int32_t k_high,
                          int32_t reverse, int32_t *perm, void *stream);
 
+/* Selection with activation pruning incorporated (Sec. 3.4): the windows with the lowest
+ * scores are pruned, the others split into high and low as above.  perm = high group (k_high),
+ * low group (k_low), pruned group (the rest), each in ascending window index. */
+int mixaq_select_windows3(const double *scores, int32_t B, int32_t nW, int32_t k_high, int32_t k_low,
+                          int32_t reverse, int32_t *perm, void *stream);
+
 /* One Two-Branch Swin Block (Fig. 3): gather + per-branch LayerNorm and
  * quantizers -> int8 windowed attention -> FFN -> residuals -> scatter.
  * perm: device [B,nW] from mixaq_select_windows (any order inside a group gives
@@ -142,7 +148,12 @@ int mixaq_select_windows(const double *scores, int32_t B, int32_t nW, int32_t k_
  * fully overwritten. */
 int mixaq_block_forward(const mixaq_block *blk, const float *x, const int32_t *perm, int32_t k_high,
                         float *y, void *workspace, size_t workspace_bytes, void *stream);
-/* Same, and also fills the given taps. */
+/* The block with activation pruning (Sec. 3.4): positions k_high+k_low.. of every image's perm
+ * row are pruned windows; their computation is skipped and y takes x there.  perm NULL scores
+ * and selects internally with the same three-way split. */
+int mixaq_block_forward_pruned(const mixaq_block *blk, const float *x, const int32_t *perm, int32_t k_high,
+                               int32_t k_low, float *y, void *workspace, size_t workspace_bytes, void *stream);
+/* Same as mixaq_block_forward, and also fills the given taps. */
 int mixaq_block_forward_taps(const mixaq_block *blk, const float *x, const int32_t *perm, int32_t k_high,
                              float *y, void *workspace, size_t workspace_bytes, void *stream,
                              const mixaq_taps *taps);

@@ -178,15 +178,27 @@ int orc_score_windows(const orc_desc *d, const orc_shared *sh, const float *x, d
  * high group.  reading: ties go to the lower window index; perm lists the high
  * group then the low group, each in ascending window index.  reverse != 0
  * inverts the importance order (the worst-case window selection of the robustness study, Sec. 4.1). */
+int orc_select_windows3(const double *scores, int32_t B, int32_t nW, int32_t k_high, int32_t k_low,
+                        int32_t reverse, int32_t *perm);
+
 int orc_select_windows(const double *scores, int32_t B, int32_t nW, int32_t k_high,
                        int32_t reverse, int32_t *perm)
 {
+    return orc_select_windows3(scores, B, nW, k_high, nW - k_high, reverse, perm);
+}
+
+/* Selection with activation pruning (Sec. 3.4): the windows with the lowest scores are pruned,
+ * the rest is split as before.  perm = high group, low group (k_low windows), pruned group, each
+ * in ascending window index. */
+int orc_select_windows3(const double *scores, int32_t B, int32_t nW, int32_t k_high, int32_t k_low,
+                        int32_t reverse, int32_t *perm)
+{
     if (!scores || !perm) return ORC_E_NULL;
-    if (B < 1 || nW < 1 || k_high < 0 || k_high > nW) return ORC_E_SHAPE;
+    if (B < 1 || nW < 1 || k_high < 0 || k_low < 0 || k_high + k_low > nW) return ORC_E_SHAPE;
     for (int b = 0; b < B; ++b) {
         const double *s = scores + (size_t)b * nW;
         int32_t *p = perm + (size_t)b * nW;
-        int nh = 0, nl = 0;
+        int nh = 0, nl = 0, np = 0;
         for (int w = 0; w < nW; ++w) {
             int rank = 0;                         /* windows strictly ahead of w */
             for (int v = 0; v < nW; ++v) {
@@ -194,7 +206,9 @@ int orc_select_windows(const double *scores, int32_t B, int32_t nW, int32_t k_hi
                 int ahead = reverse ? (s[v] < s[w]) : (s[v] > s[w]);
                 if (ahead || (s[v] == s[w] && v < w)) ++rank;
             }
-            if (rank < k_high) p[nh++] = w; else p[k_high + nl++] = w;
+            if (rank < k_high) p[nh++] = w;
+            else if (rank < k_high + k_low) p[k_high + nl++] = w;
+            else p[k_high + k_low + np++] = w;
         }
     }
     return ORC_OK;
@@ -406,21 +420,37 @@ static int check_params(const orc_desc *d, const orc_shared *sh, const orc_branc
 /* One Two-Branch Swin Block (Fig. 3).  perm == NULL: score and select here with
  * k_high windows per image in the high branch.  threads > 1 only splits the
  * independent windows over OpenMP threads; the arithmetic is unchanged. */
+int orc_block_forward_pruned(const orc_desc *d, const orc_shared *sh, const orc_branch br[2], const float *x,
+                             const int32_t *perm, int32_t k_high, int32_t k_low, float *y, const orc_taps *taps,
+                             int32_t threads);
+
 int orc_block_forward(const orc_desc *d, const orc_shared *sh, const orc_branch br[2], const float *x,
                       const int32_t *perm, int32_t k_high, float *y, const orc_taps *taps, int32_t threads)
+{
+    int32_t nW;
+    int rc = orc_num_windows(d, &nW);
+    if (rc) return rc;
+    return orc_block_forward_pruned(d, sh, br, x, perm, k_high, nW - k_high, y, taps, threads);
+}
+
+/* Block with activation pruning incorporated (Sec. 3.4): positions k_high+k_low.. of perm are
+ * pruned windows; their computation is skipped and their features are forwarded unchanged. */
+int orc_block_forward_pruned(const orc_desc *d, const orc_shared *sh, const orc_branch br[2], const float *x,
+                             const int32_t *perm, int32_t k_high, int32_t k_low, float *y, const orc_taps *taps,
+                             int32_t threads)
 {
     int rc = check_desc(d);
     if (rc) return rc;
     if ((rc = check_params(d, sh, br))) return rc;
     if (!x || !y) return ORC_E_NULL;
     int32_t nW; orc_num_windows(d, &nW);
-    if (k_high < 0 || k_high > nW) return ORC_E_SHAPE;
+    if (k_high < 0 || k_low < 0 || k_high + k_low > nW) return ORC_E_SHAPE;
     int32_t *own = NULL;
     if (!perm) {
         double *sc = (double *)malloc(sizeof(double) * d->B * nW);
         own = (int32_t *)malloc(sizeof(int32_t) * d->B * nW);
         rc = orc_score_windows(d, sh, x, sc);
-        if (!rc) rc = orc_select_windows(sc, d->B, nW, k_high, 0, own);
+        if (!rc) rc = orc_select_windows3(sc, d->B, nW, k_high, k_low, 0, own);
         free(sc);
         if (rc) { free(own); return rc; }
         perm = own;
@@ -431,8 +461,17 @@ int orc_block_forward(const orc_desc *d, const orc_shared *sh, const orc_branch 
     for (long s = 0; s < total; ++s) {
         int b = (int)(s / nW), j = (int)(s % nW);
         int hi = j < k_high;
-        process_slot(d, sh, &br[hi ? 0 : 1], hi ? d->act_bits_high : d->act_bits_low, x, b,
-                     perm[s], (size_t)s, y, taps);
+        if (j < k_high + k_low) {
+            process_slot(d, sh, &br[hi ? 0 : 1], hi ? d->act_bits_high : d->act_bits_low, x, b,
+                         perm[s], (size_t)s, y, taps);
+        } else {                                         /* pruned: forward the features */
+            for (int t = 0; t < d->window * d->window; ++t) {
+                int r, c;
+                if (!orc_token_source(d, perm[s], t, &r, &c)) continue;
+                size_t off = (((size_t)b * d->H + r) * d->W + c) * d->C;
+                memcpy(y + off, x + off, sizeof(float) * d->C);
+            }
+        }
     }
     free(own);
     return ORC_OK;

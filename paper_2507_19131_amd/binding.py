@@ -73,6 +73,10 @@ def load():
         L.mixaq_block_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                           C.c_size_t, C.c_void_p]
         L.mixaq_block_forward_taps.argtypes = L.mixaq_block_forward.argtypes + [C.c_void_p]
+        L.mixaq_select_windows3.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                            C.c_void_p]
+        L.mixaq_block_forward_pruned.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                                 C.c_void_p, C.c_size_t, C.c_void_p]
         L.mixaq_block_forward_profile.argtypes = L.mixaq_block_forward.argtypes + [C.c_int32, C.POINTER(C.c_float)]
         L.mixaq_block_set_fused.argtypes = [C.c_void_p, C.c_int32]
         L.mixaq_kernel_name.restype = C.c_char_p
@@ -152,6 +156,17 @@ def mixaq_score_windows(blk, x, scores, stream=None):
 def mixaq_select_windows(scores, B, nW, k_high, reverse, perm, stream=None):
     _check(load().mixaq_select_windows(_ptr(scores), B, nW, k_high, reverse, _ptr(perm), _stream(stream)))
     return perm
+
+
+def mixaq_select_windows3(scores, B, nW, k_high, k_low, reverse, perm, stream=None):
+    _check(load().mixaq_select_windows3(_ptr(scores), B, nW, k_high, k_low, reverse, _ptr(perm), _stream(stream)))
+    return perm
+
+
+def mixaq_block_forward_pruned(blk, x, perm, k_high, k_low, y, workspace, stream=None):
+    _check(load().mixaq_block_forward_pruned(blk, _ptr(x), _ptr(perm), k_high, k_low, _ptr(y), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream(stream)))
+    return y
 
 
 def mixaq_block_forward(blk, x, perm, k_high, y, workspace, stream=None):

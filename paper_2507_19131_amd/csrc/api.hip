@@ -195,11 +195,11 @@ int check_qparam(const mixaq_qparam& q, int bits, const char* name)
     return MIXAQ_OK;
 }
 
-void make_geom(const mixaq_block* b, int k_hi, Geom* G)
+void make_geom(const mixaq_block* b, int k_hi, int k_lo, Geom* G)
 {
     G->B = b->d.B; G->H = b->d.H; G->W = b->d.W; G->C = b->d.C; G->shift = b->d.shift; G->heads = b->d.heads;
     G->Hp = b->Hp; G->Wp = b->Wp; G->nWc = b->nWc; G->nW = b->nW;
-    G->k_hi = k_hi; G->k_lo = b->nW - k_hi;
+    G->k_hi = k_hi; G->k_lo = k_lo; G->n_slots = b->d.B * (k_hi + k_lo);
     G->rows_hi = b->d.B * k_hi * TOK;
     G->rows_lo = b->d.B * G->k_lo * TOK;
     G->base_lo = round_up(G->rows_hi, ROW_TILE);
@@ -237,13 +237,15 @@ struct Prof {
     int repeats = 1;          // every kernel is launched this many times between its two events
 };
 
-int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, float* y, void* workspace,
-                 size_t workspace_bytes, void* stream, const mixaq_taps* taps, Prof* prof = nullptr)
+int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, int32_t k_low, float* y,
+                 void* workspace, size_t workspace_bytes, void* stream, const mixaq_taps* taps, Prof* prof = nullptr)
 {
     if (!blk) return fail(MIXAQ_E_NULL, "block is NULL");
     if (!x || !y) return fail(MIXAQ_E_NULL, "x or y is NULL");
     if (!workspace) return fail(MIXAQ_E_NULL, "workspace is NULL");
-    if (k_high < 0 || k_high > blk->nW) return fail(MIXAQ_E_SHAPE, "k_high=%d outside 0..%d", k_high, blk->nW);
+    if (k_low < 0) k_low = blk->nW - k_high;      // no pruning
+    if (k_high < 0 || k_low < 0 || k_high + k_low > blk->nW)
+        return fail(MIXAQ_E_SHAPE, "k_high=%d, k_low=%d do not fit %d windows", k_high, k_low, blk->nW);
     if (workspace_bytes < blk->ws_bytes) return fail(MIXAQ_E_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, blk->ws_bytes);
     if ((uintptr_t)workspace & 255) return fail(MIXAQ_E_WORKSPACE, "workspace must be 256-byte aligned");
     {
@@ -254,7 +256,7 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, in
     hipStream_t st = (hipStream_t)stream;
     const mixaq_block_desc& d = blk->d;
     Geom G;
-    make_geom(blk, k_high, &G);
+    make_geom(blk, k_high, k_low, &G);
     Workspace ws;
     carve(blk, (char*)workspace, &ws);
     static const mixaq_taps no_taps = {};
@@ -268,9 +270,10 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, in
         mark(0);
         for (int r = 0; r < reps; ++r) launch_score(G, x, d.score_mode, d.ln_eps, blk->score_gamma, blk->score_beta, ws.scores, st);
         mark(1);
-        for (int r = 0; r < reps; ++r) launch_select(ws.scores, d.B, blk->nW, k_high, 0, ws.perm, st);
+        for (int r = 0; r < reps; ++r) launch_select(ws.scores, d.B, blk->nW, k_high, k_low, 0, ws.perm, st);
         perm = ws.perm;
     }
+    launch_bypass(G, perm, x, y, st);                // pruned windows (if any) are forwarded
     if (blk->fused) {
         WinArgs wa = {};
         wa.x = x; wa.perm = perm; wa.eps = d.ln_eps; wa.Wqkv = blk->qkv.Wp; wa.bias2 = blk->bias2; wa.out = ws.ao;
@@ -499,8 +502,20 @@ int mixaq_score_windows(const mixaq_block* blk, const float* x, double* scores, 
 {
     if (!blk || !x || !scores) return fail(MIXAQ_E_NULL, "block, x or scores is NULL");
     Geom G;
-    make_geom(blk, 0, &G);
+    make_geom(blk, 0, blk->nW, &G);
     launch_score(G, x, blk->d.score_mode, blk->d.ln_eps, blk->score_gamma, blk->score_beta, scores, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return MIXAQ_OK;
+}
+
+int mixaq_select_windows3(const double* scores, int32_t B, int32_t nW, int32_t k_high, int32_t k_low, int32_t reverse,
+                          int32_t* perm, void* stream)
+{
+    if (!scores || !perm) return fail(MIXAQ_E_NULL, "scores or perm is NULL");
+    if (B < 1 || nW < 1 || k_high < 0 || k_low < 0 || k_high + k_low > nW)
+        return fail(MIXAQ_E_SHAPE, "need B >= 1, nW >= 1, k_high >= 0, k_low >= 0, k_high + k_low <= nW");
+    if (nW > 4096) return fail(MIXAQ_E_SHAPE, "at most 4096 windows per image");
+    launch_select(scores, B, nW, k_high, k_low, reverse ? 1 : 0, perm, (hipStream_t)stream);
     HIP_TRY(hipGetLastError());
     return MIXAQ_OK;
 }
@@ -508,24 +523,27 @@ int mixaq_score_windows(const mixaq_block* blk, const float* x, double* scores, 
 int mixaq_select_windows(const double* scores, int32_t B, int32_t nW, int32_t k_high, int32_t reverse, int32_t* perm,
                          void* stream)
 {
-    if (!scores || !perm) return fail(MIXAQ_E_NULL, "scores or perm is NULL");
-    if (B < 1 || nW < 1 || k_high < 0 || k_high > nW) return fail(MIXAQ_E_SHAPE, "need B >= 1, nW >= 1, 0 <= k_high <= nW");
-    if (nW > 4096) return fail(MIXAQ_E_SHAPE, "at most 4096 windows per image");
-    launch_select(scores, B, nW, k_high, reverse ? 1 : 0, perm, (hipStream_t)stream);
-    HIP_TRY(hipGetLastError());
-    return MIXAQ_OK;
+    if (k_high < 0 || k_high > nW) return fail(MIXAQ_E_SHAPE, "need 0 <= k_high <= nW");
+    return mixaq_select_windows3(scores, B, nW, k_high, nW - k_high, reverse, perm, stream);
 }
 
 int mixaq_block_forward(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, float* y,
                         void* workspace, size_t workspace_bytes, void* stream)
 {
-    return forward_impl(blk, x, perm, k_high, y, workspace, workspace_bytes, stream, nullptr);
+    return forward_impl(blk, x, perm, k_high, -1, y, workspace, workspace_bytes, stream, nullptr);
+}
+
+int mixaq_block_forward_pruned(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, int32_t k_low,
+                               float* y, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (k_low < 0) return fail(MIXAQ_E_SHAPE, "k_low must not be negative");
+    return forward_impl(blk, x, perm, k_high, k_low, y, workspace, workspace_bytes, stream, nullptr);
 }
 
 int mixaq_block_forward_taps(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, float* y,
                              void* workspace, size_t workspace_bytes, void* stream, const mixaq_taps* taps)
 {
-    return forward_impl(blk, x, perm, k_high, y, workspace, workspace_bytes, stream, taps);
+    return forward_impl(blk, x, perm, k_high, -1, y, workspace, workspace_bytes, stream, taps);
 }
 
 int mixaq_block_set_fused(mixaq_block* blk, int32_t enable)
@@ -552,7 +570,7 @@ int mixaq_block_forward_profile(const mixaq_block* blk, const float* x, const in
     Prof prof;
     for (int i = 0; i <= MIXAQ_NUM_KERNELS; ++i) HIP_TRY(hipEventCreate(&prof.ev[i]));
     prof.repeats = repeats < 1 ? 1 : repeats;
-    int rc = forward_impl(blk, x, perm, k_high, y, workspace, workspace_bytes, stream, nullptr, &prof);
+    int rc = forward_impl(blk, x, perm, k_high, -1, y, workspace, workspace_bytes, stream, nullptr, &prof);
     if (rc == MIXAQ_OK && hipStreamSynchronize((hipStream_t)stream) != hipSuccess) rc = fail(MIXAQ_E_HIP, "stream synchronisation failed");
     for (int i = 0; i < MIXAQ_NUM_KERNELS; ++i) kernel_ms[i] = 0.0f;
     if (rc == MIXAQ_OK)

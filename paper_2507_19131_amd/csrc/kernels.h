@@ -115,7 +115,8 @@ void launch_window(const Geom& G, const WinArgs& A, hipStream_t st);
 void launch_token(const Geom& G, const TokArgs& A, hipStream_t st);
 bool launch_score(const Geom& G, const float* x, int mode, float eps, const float* gm, const float* bt, double* scores,
                   hipStream_t st);
-void launch_select(const double* scores, int B, int nW, int k_hi, int reverse, int* perm, hipStream_t st);
+void launch_select(const double* scores, int B, int nW, int k_hi, int k_lo, int reverse, int* perm, hipStream_t st);
+void launch_bypass(const Geom& G, const int* perm, const float* x, float* y, hipStream_t st);
 bool launch_ln_quant(const Geom& G, const LnArgs& A, bool gather, hipStream_t st);
 void launch_gemm(const Geom& G, const GemmArgs& A, int epi, hipStream_t st);
 void launch_attn(const Geom& G, const AttnArgs& A, hipStream_t st);

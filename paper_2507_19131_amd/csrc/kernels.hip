@@ -94,8 +94,8 @@ __global__ __launch_bounds__(256) void score_kernel(Geom G, const float* __restr
 // overwrites perm with the high group then the low group, both in ascending index.
 // Rank: a wave ranks four windows at once, its lanes stride over the candidates held in LDS.
 constexpr int RANK_WPB = 16;                          // windows ranked per workgroup (4 per wave)
-__global__ __launch_bounds__(256) void select_rank_kernel(const double* __restrict__ scores, int nW, int k_hi, int reverse,
-                                                          int* __restrict__ perm)
+__global__ __launch_bounds__(256) void select_rank_kernel(const double* __restrict__ scores, int nW, int k_hi, int k_lo,
+                                                          int reverse, int* __restrict__ perm)
 {
     extern __shared__ double rsc[];                   // all scores of the image
     const int b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -120,22 +120,22 @@ __global__ __launch_bounds__(256) void select_rank_kernel(const double* __restri
     for (int q = 0; q < Q; ++q) {
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) rank[q] += __shfl_xor(rank[q], o, 64);
-        if (lane == 0 && w0 + q < nW) perm[(size_t)b * nW + w0 + q] = rank[q] < k_hi ? 1 : 0;
+        if (lane == 0 && w0 + q < nW) perm[(size_t)b * nW + w0 + q] = rank[q] < k_hi ? 0 : (rank[q] < k_hi + k_lo ? 1 : 2);
     }
 }
 
-__global__ __launch_bounds__(1024) void select_place_kernel(int nW, int k_hi, int* __restrict__ perm)
+__global__ __launch_bounds__(1024) void select_place_kernel(int nW, int k_hi, int k_lo, int* __restrict__ perm)
 {
     extern __shared__ int smi[];
-    int* flag = smi;                                  // [nW]
-    int* wsum = smi + nW;                             // [16] per-wave totals
+    int* grp = smi;                                   // [nW] group of every window: 0 high, 1 low, 2 pruned
+    int* wsum = smi + nW;                             // [16] per-wave totals, (high << 16) | low
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int i = tid; i < nW; i += 1024) flag[i] = perm[(size_t)b * nW + i];
+    for (int i = tid; i < nW; i += 1024) grp[i] = perm[(size_t)b * nW + i];
     __syncthreads();
     const int chunk = (nW + 1023) / 1024;
     const int lo = min(tid * chunk, nW), hi = min(lo + chunk, nW);
     int cnt = 0;
-    for (int i = lo; i < hi; ++i) cnt += flag[i];
+    for (int i = lo; i < hi; ++i) cnt += grp[i] == 0 ? 0x10000 : (grp[i] == 1 ? 1 : 0);
     int incl = cnt;                                   // inclusive scan inside the wave
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) { int t = __shfl_up(incl, o, 64); if (lane >= o) incl += t; }
@@ -143,11 +143,36 @@ __global__ __launch_bounds__(1024) void select_place_kernel(int nW, int k_hi, in
     __syncthreads();
     int before = 0;
     for (int k = 0; k < wave; ++k) before += wsum[k];
-    int nh = before + incl - cnt;                     // high windows before this chunk
+    const int ex = before + incl - cnt;
+    int nh = ex >> 16, nl = ex & 0xffff;              // high / low windows before this chunk
     for (int i = lo; i < hi; ++i) {
-        int nl = i - nh;                              // low windows before i
-        if (flag[i]) perm[(size_t)b * nW + nh++] = i;
-        else perm[(size_t)b * nW + k_hi + nl] = i;
+        const int np = i - nh - nl;                   // pruned windows before i
+        const int g = grp[i];
+        if (g == 0) perm[(size_t)b * nW + nh++] = i;
+        else if (g == 1) perm[(size_t)b * nW + k_hi + nl++] = i;
+        else perm[(size_t)b * nW + k_hi + k_lo + np] = i;
+    }
+}
+
+// ------------------------------------------------------------------ pruned windows
+// Activation pruning (paper Sec. 3.4): the windows after the high and low groups in perm are
+// skipped by the block and their features are forwarded.  One workgroup per pruned window.
+__global__ __launch_bounds__(256) void bypass_kernel(Geom G, const int* __restrict__ perm, const float* __restrict__ x,
+                                                     float* __restrict__ y)
+{
+    const int kept = G.k_hi + G.k_lo, n_pruned = G.nW - kept;
+    const int b = blockIdx.x / n_pruned, jpos = kept + blockIdx.x % n_pruned;
+    const int w = perm[b * G.nW + jpos];
+    const int wr = w / G.nWc, wc = w - wr * G.nWc;
+    const int c4 = G.C / 4;
+    for (int i = threadIdx.x; i < TOK * c4; i += 256) {
+        const int t = i / c4, k = i - t * c4, tr = t / WS, tc = t - tr * WS;
+        int pr = wr * WS + tr + G.shift; if (pr >= G.Hp) pr -= G.Hp;
+        int pc = wc * WS + tc + G.shift; if (pc >= G.Wp) pc -= G.Wp;
+        if (pr < G.H && pc < G.W) {
+            const size_t off = ((size_t)(b * G.H + pr) * G.W + pc) * G.C + k * 4;
+            *(float4*)(y + off) = *(const float4*)(x + off);
+        }
     }
 }
 
@@ -434,7 +459,7 @@ __global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
     __shared__ __attribute__((aligned(16))) int csum[4][HD];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 31, g = lane >> 5;
     const int item = blockIdx.x * 4 + wave;                              // slot * heads + head
-    if (item >= G.B * G.nW * G.heads) return;
+    if (item >= G.n_slots * G.heads) return;
     const int slot = item / G.heads, head = item - slot * G.heads;
     int branch, row0, canon_slot;
     slot_info(G, slot, branch, row0, canon_slot);
@@ -828,6 +853,7 @@ template <int LPT, int NV>
 static void launch_ln_t(const Geom& G, const LnArgs& A, bool gather, hipStream_t st)
 {
     constexpr int TP = 256 / LPT;
+    if (G.rows_total == 0) return;
     dim3 grid((G.rows_total + TP - 1) / TP);
     if (gather) hipLaunchKernelGGL((ln_quant_kernel<LPT, NV, true>), grid, dim3(256), 0, st, G, A);
     else hipLaunchKernelGGL((ln_quant_kernel<LPT, NV, false>), grid, dim3(256), 0, st, G, A);
@@ -860,11 +886,17 @@ bool launch_score(const Geom& G, const float* x, int mode, float eps, const floa
     return true;
 }
 
-void launch_select(const double* scores, int B, int nW, int k_hi, int reverse, int* perm, hipStream_t st)
+void launch_bypass(const Geom& G, const int* perm, const float* x, float* y, hipStream_t st)
+{
+    const int n_pruned = G.nW - G.k_hi - G.k_lo;
+    if (n_pruned > 0) hipLaunchKernelGGL(bypass_kernel, dim3(G.B * n_pruned), dim3(256), 0, st, G, perm, x, y);
+}
+
+void launch_select(const double* scores, int B, int nW, int k_hi, int k_lo, int reverse, int* perm, hipStream_t st)
 {
     hipLaunchKernelGGL(select_rank_kernel, dim3((nW + RANK_WPB - 1) / RANK_WPB, B), dim3(256), (size_t)nW * 8, st, scores, nW, k_hi,
-                       reverse, perm);
-    hipLaunchKernelGGL(select_place_kernel, dim3(B), dim3(1024), (size_t)nW * 4 + 64, st, nW, k_hi, perm);
+                       k_lo, reverse, perm);
+    hipLaunchKernelGGL(select_place_kernel, dim3(B), dim3(1024), (size_t)nW * 4 + 64, st, nW, k_hi, k_lo, perm);
 }
 
 bool launch_ln_quant(const Geom& G, const LnArgs& A, bool gather, hipStream_t st)
@@ -879,6 +911,7 @@ template <int EPI>
 static void launch_gemm_e(const Geom& G, const GemmArgs& A0, hipStream_t st)
 {
     GemmArgs A = A0;
+    if (G.rows_total == 0) return;
     const int tiles = G.rows_total / ROW_TILE, gx = (tiles + 3) / 4, NB = A.N / 32;
     int split = 1;                                   // split the channel blocks until the grid fills the chip
     while (gx * split < 1024 && split < NB) ++split;
@@ -908,7 +941,8 @@ bool fused_supported(int C, int mlp_ratio) { return (C == 96 || C == 128 || C ==
 
 void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
 {
-    dim3 grid(G.B * G.nW);
+    if (G.n_slots == 0) return;
+    dim3 grid(G.n_slots);
 #define WIN_CASE(NH)                                                                                     \
     if (A.taps) hipLaunchKernelGGL((window_kernel<NH, true>), grid, dim3(NH * 64), 0, st, G, A);        \
     else hipLaunchKernelGGL((window_kernel<NH, false>), grid, dim3(NH * 64), 0, st, G, A);              \
@@ -924,6 +958,7 @@ void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
 
 void launch_token(const Geom& G, const TokArgs& A, hipStream_t st)
 {
+    if (G.rows_total == 0) return;
     dim3 grid(G.rows_total / 32);
 #define TOK_CASE(NH)                                                                                     \
     if (A.taps) hipLaunchKernelGGL((token_kernel<NH, true>), grid, dim3(NH * 64), 0, st, G, A);         \
@@ -940,7 +975,8 @@ void launch_token(const Geom& G, const TokArgs& A, hipStream_t st)
 
 void launch_attn(const Geom& G, const AttnArgs& A, hipStream_t st)
 {
-    const int items = G.B * G.nW * G.heads;
+    const int items = G.n_slots * G.heads;
+    if (items == 0) return;
     hipLaunchKernelGGL(attn_kernel, dim3((items + 3) / 4), dim3(256), 0, st, G, A);
 }
 

@@ -98,7 +98,8 @@ __device__ __forceinline__ int mfma_row(int r, int g) { return (r >> 2) * 8 + g 
 struct Geom {
     int B, H, W, C, shift, heads;
     int Hp, Wp, nWc, nW;
-    int k_hi, k_lo;
+    int k_hi, k_lo;              // windows per image in the high / low branch (the rest is pruned)
+    int n_slots;                 // B*(k_hi+k_lo) windows that are computed
     int rows_hi, rows_lo;        // valid rows per region (B*k*49)
     int base_lo;                 // first row of the low region (multiple of ROW_TILE)
     int rows_total;              // multiple of ROW_TILE

@@ -134,17 +134,22 @@ def score_windows(inp, x, shift=None):
     return out
 
 
-def select_windows(scores, k_high, reverse=0):
+def select_windows(scores, k_high, reverse=0, k_low=None):
     B, nW = scores.shape
     perm = np.zeros((B, nW), dtype=np.int32)
     sc = np.ascontiguousarray(scores, dtype=np.float64)
-    rc = lib().orc_select_windows(sc.ctypes.data_as(C.POINTER(C.c_double)), B, nW, k_high, reverse, _p(perm, _I32))
+    if k_low is None:
+        rc = lib().orc_select_windows(sc.ctypes.data_as(C.POINTER(C.c_double)), B, nW, k_high, reverse, _p(perm, _I32))
+    else:
+        rc = lib().orc_select_windows3(sc.ctypes.data_as(C.POINTER(C.c_double)), B, nW, k_high, k_low, reverse,
+                                       _p(perm, _I32))
     assert rc == 0, rc
     return perm
 
 
-def block_forward(inp, x, perm, k_high, shift=None, want_taps=(), threads=8):
-    """Runs the oracle; returns (y, taps dict).  perm None = score+select inside."""
+def block_forward(inp, x, perm, k_high, shift=None, want_taps=(), threads=8, k_low=None):
+    """Runs the oracle; returns (y, taps dict).  perm None = score+select inside.
+    k_low given: windows beyond k_high+k_low in perm are pruned (features forwarded)."""
     spec = inp.spec
     d, sh, br = make_desc(spec, shift), make_shared(inp.shared), make_branches(inp.branches)
     y = np.full((spec.B, spec.H, spec.W, spec.C), np.nan, dtype=np.float32)
@@ -157,8 +162,12 @@ def block_forward(inp, x, perm, k_high, shift=None, want_taps=(), threads=8):
     x = np.ascontiguousarray(x, dtype=np.float32)
     if perm is not None:
         perm = np.ascontiguousarray(perm, dtype=np.int32)
-    rc = lib().orc_block_forward(C.byref(d), C.byref(sh), br, _p(x, _FP), _p(perm, _I32), int(k_high), _p(y, _FP),
-                                 C.byref(tp) if taps else None, int(threads))
+    if k_low is None:
+        rc = lib().orc_block_forward(C.byref(d), C.byref(sh), br, _p(x, _FP), _p(perm, _I32), int(k_high), _p(y, _FP),
+                                     C.byref(tp) if taps else None, int(threads))
+    else:
+        rc = lib().orc_block_forward_pruned(C.byref(d), C.byref(sh), br, _p(x, _FP), _p(perm, _I32), int(k_high),
+                                            int(k_low), _p(y, _FP), C.byref(tp) if taps else None, int(threads))
     assert rc == 0, rc
     return y, taps
 

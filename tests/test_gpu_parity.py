@@ -108,3 +108,32 @@ def test_error_paths_do_not_launch():
         with pytest.raises(M.MixaqError) as e:
             M.mixaq_block_forward(gb.blk, xt, None, k, xt, gb.ws)
         assert e.value.code == -2
+
+
+@pytest.mark.parametrize("fused", [True, False])
+@pytest.mark.parametrize("shift,kh_frac,kl_frac", [(0, 0.3, 0.4), (3, 0.25, 0.5), (3, 0.0, 0.0), (0, 0.5, 0.0)])
+def test_activation_pruning_matches_oracle(shift, kh_frac, kl_frac, fused):
+    """Three-way split (Sec. 3.4): high, low, pruned windows; pruned features are forwarded."""
+    import oracle_api as O
+    from paper_2507_19131_amd import binding as M
+    spec, inp, x, _ = _case(2, 26, 33, 96, 3, shift, 0.5, 31, blobs=True)
+    nW = spec.nW
+    kh, kl = int(kh_frac * nW), int(kl_frac * nW)
+    print("pruning case shift", shift, "k_high", kh, "k_low", kl, "fused", fused, flush=True)
+    dev = torch.device("cuda:0")
+    xt = torch.from_numpy(x).to(dev)
+    with gh.GpuBlock(inp, fused=fused) as gb:
+        scores = torch.empty((2, nW), dtype=torch.float64, device=dev)
+        perm = torch.empty((2, nW), dtype=torch.int32, device=dev)
+        M.mixaq_score_windows(gb.blk, xt, scores)
+        M.mixaq_select_windows3(scores, 2, nW, kh, kl, 0, perm)
+        y = torch.full_like(xt, float("nan"))
+        M.mixaq_block_forward_pruned(gb.blk, xt, perm, kh, kl, y, gb.ws)
+        y2 = torch.full_like(xt, float("nan"))
+        M.mixaq_block_forward_pruned(gb.blk, xt, None, kh, kl, y2, gb.ws)          # internal three-way selection
+        torch.cuda.synchronize()
+    o_perm = O.select_windows(O.score_windows(inp, x), kh, k_low=kl)
+    assert np.array_equal(perm.cpu().numpy(), o_perm)
+    oy, _ = O.block_forward(inp, x, o_perm, kh, k_low=kl)
+    assert np.array_equal(y.cpu().numpy(), oy)
+    assert torch.equal(y, y2)

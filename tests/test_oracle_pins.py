@@ -389,3 +389,36 @@ def test_error_codes():
     assert L.orc_block_forward(C.byref(bad), C.byref(sh), br, x.ctypes.data_as(O._FP), None, 1, y.ctypes.data_as(O._FP), None, 1) == -2
     assert L.orc_block_forward(C.byref(d), C.byref(sh), br, None, None, 1, y.ctypes.data_as(O._FP), None, 1) == -1
     assert L.orc_block_forward(C.byref(d), C.byref(sh), br, x.ctypes.data_as(O._FP), None, 99, y.ctypes.data_as(O._FP), None, 1) == -2
+
+
+# ---------------------------------------------------------------- activation pruning (Sec. 3.4)
+def test_pruned_windows_are_forwarded_and_the_rest_unchanged():
+    """Pruning the lowest-score windows: their features pass through untouched; the other windows
+    give exactly what they give without pruning when the block is not shifted (windows are
+    independent), and selection puts the lowest scores in the pruned group."""
+    spec, inp, x = _setup(28, 35, 64, 2, 0, 31, Bn=2)
+    nW, kh, kl = spec.nW, 6, 8
+    sc = O.score_windows(inp, x)
+    perm3 = O.select_windows(sc, kh, k_low=kl)
+    for b in range(2):
+        order = np.lexsort((np.arange(nW), -sc[b]))
+        assert np.array_equal(perm3[b, :kh], np.sort(order[:kh]))
+        assert np.array_equal(perm3[b, kh:kh + kl], np.sort(order[kh:kh + kl]))
+        assert np.array_equal(perm3[b, kh + kl:], np.sort(order[kh + kl:]))
+    y3, _ = O.block_forward(inp, x, perm3, kh, k_low=kl)
+    # same high group, every other window low: the un-pruned reference
+    perm2 = perm3.copy()
+    perm2[:, kh:] = np.sort(perm3[:, kh:], axis=1)
+    y2, _ = O.block_forward(inp, x, perm2, kh)
+    win3, _ = O.gather_windows(spec, y3, perm3)
+    win2, _ = O.gather_windows(spec, y2, perm3)
+    winx, _ = O.gather_windows(spec, x, perm3)
+    win3, win2, winx = (a.reshape(2, nW, 49, 64) for a in (win3, win2, winx))
+    assert np.array_equal(win3[:, kh + kl:], winx[:, kh + kl:])            # forwarded
+    assert np.array_equal(win3[:, :kh + kl], win2[:, :kh + kl])            # computed as before
+    assert not np.array_equal(win2[:, kh + kl:], winx[:, kh + kl:])
+    # k_low = nW - k_high is the plain block; everything pruned is the identity
+    ya, _ = O.block_forward(inp, x, perm2, kh, k_low=nW - kh)
+    assert np.array_equal(ya, y2)
+    yi, _ = O.block_forward(inp, x, perm2, 0, k_low=0)
+    assert np.array_equal(yi, x)
