@@ -158,6 +158,30 @@ int mixaq_block_forward_taps(const mixaq_block *blk, const float *x, const int32
                              float *y, void *workspace, size_t workspace_bytes, void *stream,
                              const mixaq_taps *taps);
 
+/* ---- host-only helpers (no GPU work) ------------------------------------------------------- */
+
+/* Equivalent activation bits (appendix "Calculation of Equivalent Activation Bits"):
+ *   act_bits_eq = act_bits_base * (sum_i f_i*gmacs[i] + c_gmacs) / (sum_i gmacs[i] + c_gmacs),
+ * f_i = 1 - compress_ratio[i]/2 for MixA-Q (a low-bit window costs half).  prune_ratio (may be
+ * NULL) adds activation pruning, f_i = 1 - prune_ratio[i] - compress_ratio[i]/2 (a pruned window
+ * costs nothing; ratios are fractions of ALL windows); compress_ratio = 0 with a prune ratio gives
+ * the pure-pruning formula f_i = 1 - r.  gmacs: GMACs per pair of blocks, c_gmacs: the layers
+ * the method cannot save.  All pointers host. */
+int mixaq_equivalent_act_bits(int32_t n_pairs, const double *gmacs, double c_gmacs, const double *compress_ratio,
+                              const double *prune_ratio, double act_bits_base, double *act_bits_eq);
+/* Bit operations in units of 1e12: GMACs * act_bits * other_operand_bits (the paper's tables hold
+ * the other operand at 32, Sec. 4.1). */
+int mixaq_bops_tera(double total_gmacs, double act_bits, double other_operand_bits, double *bops_tera);
+
+/* Uniform-sum compression-ratio sampling (Algorithm 1): a target sum S (in tenths) uniform on
+ * [10*s_min, 10*s_max], ratios from a flat Dirichlet scaled to S, re-drawn until none exceeds
+ * `upper`, rounded to tenths with the largest-remainder method so that they still sum to S/10.
+ * The random numbers come from the caller: uniforms[] in (0,1); one is used for S and n per
+ * Dirichlet draw (exponential spacings).  n_used (may be NULL) receives how many were consumed;
+ * MIXAQ_E_WORKSPACE if they run out.  ratios: host [n]. */
+int mixaq_sample_ratios(int32_t n, double s_min, double s_max, double upper, const double *uniforms, size_t n_uniforms,
+                        size_t *n_used, double *ratios);
+
 /* Chooses between the two implementations of the forward call: the fused pair of
  * kernels (one workgroup per window for gather/LN1/QKV/attention, one per 32-row
  * tile for proj/LN2/FFN/scatter; the default where supported: C <= 256, mlp_ratio

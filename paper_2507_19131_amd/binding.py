@@ -186,6 +186,41 @@ def mixaq_block_forward_taps(blk, x, perm, k_high, y, workspace, taps, stream=No
 NUM_KERNELS = 11
 
 
+def _darr(values):
+    return (C.c_double * len(values))(*[float(v) for v in values])
+
+
+def mixaq_equivalent_act_bits(gmacs, c_gmacs, compress_ratio, prune_ratio, act_bits_base):
+    out = C.c_double()
+    L = load()
+    L.mixaq_equivalent_act_bits.argtypes = [C.c_int32, C.c_void_p, C.c_double, C.c_void_p, C.c_void_p, C.c_double,
+                                            C.POINTER(C.c_double)]
+    _check(L.mixaq_equivalent_act_bits(len(gmacs), _darr(gmacs), float(c_gmacs), _darr(compress_ratio),
+                                       _darr(prune_ratio) if prune_ratio is not None else None, float(act_bits_base),
+                                       C.byref(out)))
+    return out.value
+
+
+def mixaq_bops_tera(total_gmacs, act_bits, other_operand_bits=32.0):
+    out = C.c_double()
+    L = load()
+    L.mixaq_bops_tera.argtypes = [C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double)]
+    _check(L.mixaq_bops_tera(float(total_gmacs), float(act_bits), float(other_operand_bits), C.byref(out)))
+    return out.value
+
+
+def mixaq_sample_ratios(n, s_min, s_max, upper, uniforms):
+    """Returns (ratios list, number of uniforms consumed)."""
+    L = load()
+    L.mixaq_sample_ratios.argtypes = [C.c_int32, C.c_double, C.c_double, C.c_double, C.c_void_p, C.c_size_t,
+                                      C.POINTER(C.c_size_t), C.c_void_p]
+    out = (C.c_double * n)()
+    used = C.c_size_t()
+    u = np.ascontiguousarray(uniforms, dtype=np.float64)
+    _check(L.mixaq_sample_ratios(n, s_min, s_max, upper, C.c_void_p(u.ctypes.data), u.size, C.byref(used), out))
+    return list(out), used.value
+
+
 def mixaq_block_set_fused(blk, enable):
     _check(load().mixaq_block_set_fused(blk, int(enable)))
 

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmixaq.so")
-SOURCES = ["api.hip", "kernels.hip"]
+SOURCES = ["api.hip", "kernels.hip", "cost_sampler.cpp"]
 # -ffp-contract=off: the pinned binary32 sequences must not be re-fused;
 # packed fp32 instructions are disabled for the device pass.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-ffp-contract=off", "-fPIC", "-shared",
@@ -14,7 +14,7 @@ FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-ffp-contract=off", "-fP
 
 def build(verbose=False):
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = ["hipcc"] + FLAGS + ["-o", LIB] + srcs
+    cmd = ["hipcc"] + FLAGS + ["-x", "hip", "-o", LIB] + srcs
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)

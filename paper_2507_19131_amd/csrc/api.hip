@@ -14,10 +14,10 @@
 
 using namespace mixaq;
 
-namespace {
-
+namespace mixaq {
 thread_local char g_err[512] = "";
 
+// records the calling thread's error message and returns `code`
 int fail(int code, const char* fmt, ...)
 {
     va_list ap;
@@ -26,6 +26,9 @@ int fail(int code, const char* fmt, ...)
     va_end(ap);
     return code;
 }
+}  // namespace mixaq
+
+namespace {
 
 #define HIP_TRY(expr)                                                                                   \
     do {                                                                                                \
