@@ -109,7 +109,7 @@ const char *mixaq_last_error(void);
 /* Windows per image of the padded map. */
 int mixaq_num_windows(const mixaq_block_desc *desc, int32_t *nW_per_image);
 /* k_high = floor(keep_ratio*nW + 1/2) clamped to [0,nW] (Sec. 3.3: the ratio is a
- * proportion of windows). */
+ * share of the windows). */
 int mixaq_keep_count(int32_t nW, double keep_ratio, int32_t *k_high);
 
 /* Builds a block: validates, copies the quantizer and LayerNorm parameters and

@@ -16,8 +16,8 @@
 #include <math.h>
 #include <stdint.h>
 
-/* Uniform affine quantizer, x_hat = scale*(q - zero_point)  (Sec. 3.2: "step
- * sizes and zero points" per branch).  q = clamp(round(v*inv_s + z)), rounding
+/* Uniform affine quantizer, x_hat = scale*(q - zero_point)  (Sec. 3.2 keeps one
+ * step size and zero point per branch).  q = clamp(round(v*inv_s + z)), rounding
  * half-to-even, evaluated exactly: the product of two binary32 numbers fits
  * binary64, and the integer zero point is added to its integer part so that no
  * bit is lost before the rounding decision. */

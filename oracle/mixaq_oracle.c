@@ -106,7 +106,7 @@ int orc_num_windows(const orc_desc *d, int32_t *nW)
 }
 
 /* reading: number of high-branch windows per image = keep ratio times window
- * count, rounded half up (Sec. 3.3 gives the ratio as a "proportion of windows"). */
+ * count, rounded half up (Sec. 3.3 defines the ratio as a share of the windows). */
 int orc_keep_count(int32_t nW, double keep_ratio, int32_t *k_high)
 {
     if (!k_high) return ORC_E_NULL;
