@@ -129,22 +129,25 @@ int mixaq_block_workspace_bytes(const mixaq_block *blk, size_t *bytes);
 int mixaq_score_windows(const mixaq_block *blk, const float *x, double *scores, void *stream);
 
 /* Selection (Sec. 3.2): per image, the k_high windows with the highest score
- * (ties: lower index first) form the high group.  perm: device int32 [B,nW] =
- * high group then low group, each in ascending window index.  reverse != 0
- * inverts the order of importance (worst-case window selection of the robustness study, Sec. 4.1). */
+ * form the high group.  perm: device int32 [B,nW] = the windows of each image in
+ * order of decreasing score (ties: lower index first); the high group is the
+ * first k_high entries, the low group the rest.  reverse != 0 inverts the order
+ * of importance (worst-case window selection of the robustness study, Sec. 4.1).
+ * k_high only takes part in validation: the list is the same for every split. */
 int mixaq_select_windows(const double *scores, int32_t B, int32_t nW, int32_t k_high,
                          int32_t reverse, int32_t *perm, void *stream);
 
 /* Selection with activation pruning incorporated (Sec. 3.4): the windows with the lowest
- * scores are pruned, the others split into high and low as above.  perm = high group (k_high),
- * low group (k_low), pruned group (the rest), each in ascending window index. */
+ * scores are pruned, the others split into high and low as above.  perm is the same sorted list:
+ * high group = first k_high entries, low group = next k_low, pruned group = the rest. */
 int mixaq_select_windows3(const double *scores, int32_t B, int32_t nW, int32_t k_high, int32_t k_low,
                           int32_t reverse, int32_t *perm, void *stream);
 
 /* One Two-Branch Swin Block (Fig. 3): gather + per-branch LayerNorm and
  * quantizers -> int8 windowed attention -> FFN -> residuals -> scatter.
- * perm: device [B,nW] from mixaq_select_windows (any order inside a group gives
- * the same y), or NULL to score and select x internally.  y: device [B,H,W,C],
+ * perm: device [B,nW], per image the high group in its first k_high entries (any
+ * order inside a group gives the same y; mixaq_select_windows produces such a
+ * list), or NULL to score and select x internally.  y: device [B,H,W,C],
  * fully overwritten. */
 int mixaq_block_forward(const mixaq_block *blk, const float *x, const int32_t *perm, int32_t k_high,
                         float *y, void *workspace, size_t workspace_bytes, void *stream);

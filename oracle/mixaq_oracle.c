@@ -175,9 +175,10 @@ int orc_score_windows(const orc_desc *d, const orc_shared *sh, const float *x, d
 }
 
 /* Selection (Sec. 3.2): the k_high windows with the highest scores form the
- * high group.  reading: ties go to the lower window index; perm lists the high
- * group then the low group, each in ascending window index.  reverse != 0
- * inverts the importance order (the worst-case window selection of the robustness study, Sec. 4.1). */
+ * high group.  reading: perm lists the windows of an image in order of decreasing
+ * score, ties going to the lower window index, so the high group is its first
+ * k_high entries and the low group the rest.  reverse != 0 inverts the importance
+ * order (the worst-case window selection of the robustness study, Sec. 4.1). */
 int orc_select_windows3(const double *scores, int32_t B, int32_t nW, int32_t k_high, int32_t k_low,
                         int32_t reverse, int32_t *perm);
 
@@ -188,8 +189,8 @@ int orc_select_windows(const double *scores, int32_t B, int32_t nW, int32_t k_hi
 }
 
 /* Selection with activation pruning (Sec. 3.4): the windows with the lowest scores are pruned,
- * the rest is split as before.  perm = high group, low group (k_low windows), pruned group, each
- * in ascending window index. */
+ * the rest is split as before.  perm is the same sorted list; its first k_high entries are the high
+ * group, the next k_low the low group, the remainder is pruned. */
 int orc_select_windows3(const double *scores, int32_t B, int32_t nW, int32_t k_high, int32_t k_low,
                         int32_t reverse, int32_t *perm)
 {
@@ -198,7 +199,6 @@ int orc_select_windows3(const double *scores, int32_t B, int32_t nW, int32_t k_h
     for (int b = 0; b < B; ++b) {
         const double *s = scores + (size_t)b * nW;
         int32_t *p = perm + (size_t)b * nW;
-        int nh = 0, nl = 0, np = 0;
         for (int w = 0; w < nW; ++w) {
             int rank = 0;                         /* windows strictly ahead of w */
             for (int v = 0; v < nW; ++v) {
@@ -206,9 +206,7 @@ int orc_select_windows3(const double *scores, int32_t B, int32_t nW, int32_t k_h
                 int ahead = reverse ? (s[v] < s[w]) : (s[v] > s[w]);
                 if (ahead || (s[v] == s[w] && v < w)) ++rank;
             }
-            if (rank < k_high) p[nh++] = w;
-            else if (rank < k_high + k_low) p[k_high + nl++] = w;
-            else p[k_high + k_low + np++] = w;
+            p[rank] = w;                          /* the rank under a total order is a permutation */
         }
     }
     return ORC_OK;

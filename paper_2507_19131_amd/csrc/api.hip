@@ -118,6 +118,7 @@ struct mixaq_block {
     float* bias2 = nullptr;
     QDev q_in[2], q_qkv[2][3], q_p[2], q_ao[2], q_fc1in[2], q_fc2in[2];
     float m2[2], m_o[2];
+    float* tok_params[2] = {nullptr, nullptr};   // parameter blocks of the fused token kernel
     size_t ws_bytes = 0;
     int rows_max = 0;
     bool fused = false;        // window + token kernels instead of the seven-kernel path
@@ -273,7 +274,7 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, in
         mark(0);
         for (int r = 0; r < reps; ++r) launch_score(G, x, d.score_mode, d.ln_eps, blk->score_gamma, blk->score_beta, ws.scores, st);
         mark(1);
-        for (int r = 0; r < reps; ++r) launch_select(ws.scores, d.B, blk->nW, k_high, k_low, 0, ws.perm, st);
+        for (int r = 0; r < reps; ++r) launch_select(ws.scores, d.B, blk->nW, 0, ws.perm, st);
         perm = ws.perm;
     }
     launch_bypass(G, perm, x, y, st);                // pruned windows (if any) are forwarded
@@ -289,10 +290,7 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, in
             wa.m[br] = blk->qkv.m[br]; wa.bias[br] = blk->qkv.bias[br]; wa.negcorr[br] = blk->qkv.negcorr[br];
             for (int k = 0; k < 3; ++k) wa.q_qkv[br][k] = blk->q_qkv[br][k];
             wa.m2[br] = blk->m2[br]; wa.m_o[br] = blk->m_o[br]; wa.qp[br] = blk->q_p[br]; wa.qo[br] = blk->q_ao[br];
-            ta.p_m[br] = blk->proj.m[br]; ta.p_bias[br] = blk->proj.bias[br]; ta.p_negcorr[br] = blk->proj.negcorr[br];
-            ta.f1_m[br] = blk->fc1.m[br]; ta.f1_bias[br] = blk->fc1.bias[br]; ta.f1_negcorr[br] = blk->fc1.negcorr[br];
-            ta.f2_m[br] = blk->fc2.m[br]; ta.f2_bias[br] = blk->fc2.bias[br]; ta.f2_negcorr[br] = blk->fc2.negcorr[br];
-            ta.gamma[br] = blk->ln_gamma[1][br]; ta.beta[br] = blk->ln_beta[1][br];
+            ta.params[br] = blk->tok_params[br];
             ta.q_fc1in[br] = blk->q_fc1in[br]; ta.q_fc2in[br] = blk->q_fc2in[br];
         }
         wa.tap_a1 = tp.a_qkv_in; wa.tap_acc = tp.acc_qkv; wa.tap_qkv = tp.qkv; wa.tap_s = tp.acc_s; wa.tap_p = tp.p;
@@ -479,6 +477,22 @@ int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* 
         if ((rc = upload(b->owned, tab, &b->bias2))) return bail(rc);
     }
     b->fused = fused_supported(C, desc->mlp_ratio);
+    if (b->fused) {     // parameter blocks of the token kernel: device-to-device gathers of what was just uploaded
+        for (int br = 0; br < 2; ++br) {
+            std::vector<float> blkp((size_t)8 * C + 3 * F);
+            struct { const void* src; int n; } parts[11] = {
+                {b->proj.m[br], C}, {b->proj.bias[br], C}, {b->proj.negcorr[br], C}, {b->ln_gamma[1][br], C},
+                {b->ln_beta[1][br], C}, {b->fc2.m[br], C}, {b->fc2.bias[br], C}, {b->fc2.negcorr[br], C},
+                {b->fc1.m[br], F}, {b->fc1.bias[br], F}, {b->fc1.negcorr[br], F}};
+            size_t off = 0;
+            for (auto& pt : parts) {
+                if (hipMemcpy(blkp.data() + off, pt.src, (size_t)pt.n * 4, hipMemcpyDeviceToHost) != hipSuccess)
+                    return bail(fail(MIXAQ_E_HIP, "copy of a parameter block failed"));
+                off += pt.n;
+            }
+            if ((rc = upload(b->owned, blkp, &b->tok_params[br]))) return bail(rc);
+        }
+    }
     b->rows_max = round_up(desc->B * b->nW * TOK, ROW_TILE) + ROW_TILE;
     Workspace w;
     b->ws_bytes = carve(b, nullptr, &w);
@@ -518,7 +532,7 @@ int mixaq_select_windows3(const double* scores, int32_t B, int32_t nW, int32_t k
     if (B < 1 || nW < 1 || k_high < 0 || k_low < 0 || k_high + k_low > nW)
         return fail(MIXAQ_E_SHAPE, "need B >= 1, nW >= 1, k_high >= 0, k_low >= 0, k_high + k_low <= nW");
     if (nW > 4096) return fail(MIXAQ_E_SHAPE, "at most 4096 windows per image");
-    launch_select(scores, B, nW, k_high, k_low, reverse ? 1 : 0, perm, (hipStream_t)stream);
+    launch_select(scores, B, nW, reverse ? 1 : 0, perm, (hipStream_t)stream);
     HIP_TRY(hipGetLastError());
     return MIXAQ_OK;
 }

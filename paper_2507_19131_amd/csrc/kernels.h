@@ -98,10 +98,10 @@ struct TokArgs {                     // fused token kernel (proj + LN2 + FFN + s
     const v4i* Wproj;                // natural k order
     const v4i* W1;                   // k order of the MFMA result registers
     const v4i* W2;
-    const float* p_m[2]; const float* p_bias[2]; const int* p_negcorr[2];
-    const float* f1_m[2]; const float* f1_bias[2]; const int* f1_negcorr[2];
-    const float* f2_m[2]; const float* f2_bias[2]; const int* f2_negcorr[2];
-    const float* gamma[2]; const float* beta[2];
+    // per branch one block of 32-bit words, staged in LDS by every workgroup:
+    // [proj m | proj bias | proj negcorr | LN2 gamma | LN2 beta | fc2 m | fc2 bias | fc2 negcorr] (C words each),
+    // then [fc1 m | fc1 bias | fc1 negcorr] (4C words each); negcorr words are integers
+    const float* params[2];
     float eps;
     QDev q_fc1in[2], q_fc2in[2];
     int32_t* tap_acc_proj; float* tap_h; int8_t* tap_a2; int32_t* tap_acc_fc1; int8_t* tap_g; int32_t* tap_acc_fc2; float* tap_y;
@@ -115,7 +115,7 @@ void launch_window(const Geom& G, const WinArgs& A, hipStream_t st);
 void launch_token(const Geom& G, const TokArgs& A, hipStream_t st);
 bool launch_score(const Geom& G, const float* x, int mode, float eps, const float* gm, const float* bt, double* scores,
                   hipStream_t st);
-void launch_select(const double* scores, int B, int nW, int k_hi, int k_lo, int reverse, int* perm, hipStream_t st);
+void launch_select(const double* scores, int B, int nW, int reverse, int* perm, hipStream_t st);
 void launch_bypass(const Geom& G, const int* perm, const float* x, float* y, hipStream_t st);
 bool launch_ln_quant(const Geom& G, const LnArgs& A, bool gather, hipStream_t st);
 void launch_gemm(const Geom& G, const GemmArgs& A, int epi, hipStream_t st);

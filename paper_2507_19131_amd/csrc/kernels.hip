@@ -88,18 +88,24 @@ __global__ __launch_bounds__(256) void score_kernel(Geom G, const float* __restr
 }
 
 // ------------------------------------------------------------------ K1 select
-// Rank by counting under the total order (score descending, index ascending): a window is
-// in the high group iff fewer than k_hi windows are ahead of it.  select_rank_kernel writes
-// that flag into perm; select_place_kernel (one workgroup per image) scans the flags and
-// overwrites perm with the high group then the low group, both in ascending index.
-// Rank: a wave ranks four windows at once, its lanes stride over the candidates held in LDS.
+// Rank by counting under the total order (score descending, index ascending): the rank of a
+// window is the number of windows ahead of it, which is a permutation, so perm[rank] = window
+// lists the windows by decreasing importance; the high group is the first k_hi entries.
+// A wave ranks four windows at once, its lanes stride over the candidates held in LDS.
 constexpr int RANK_WPB = 16;                          // windows ranked per workgroup (4 per wave)
-__global__ __launch_bounds__(256) void select_rank_kernel(const double* __restrict__ scores, int nW, int k_hi, int k_lo,
-                                                          int reverse, int* __restrict__ perm)
+__global__ __launch_bounds__(256) void select_rank_kernel(const double* __restrict__ scores, int nW, int reverse,
+                                                          int* __restrict__ perm)
 {
     extern __shared__ double rsc[];                   // all scores of the image
     const int b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int i = threadIdx.x; i < nW; i += 256) rsc[i] = scores[(size_t)b * nW + i];
+    const double* sc = scores + (size_t)b * nW;
+    for (int base = 0; base < nW; base += 2048) {     // eight loads in flight per thread
+        double tmp[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) { const int i = base + threadIdx.x + k * 256; tmp[k] = i < nW ? sc[i] : 0.0; }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) { const int i = base + threadIdx.x + k * 256; if (i < nW) rsc[i] = tmp[k]; }
+    }
     __syncthreads();
     constexpr int Q = RANK_WPB / 4;                   // windows per wave, ranked together
     const int w0 = blockIdx.x * RANK_WPB + wave * Q;
@@ -108,49 +114,26 @@ __global__ __launch_bounds__(256) void select_rank_kernel(const double* __restri
     int rank[Q];
 #pragma unroll
     for (int q = 0; q < Q; ++q) { sw[q] = rsc[min(w0 + q, nW - 1)]; rank[q] = 0; }
-    for (int v = lane; v < nW; v += 64) {
-        const double sv = rsc[v];
+    const double nan = __longlong_as_double(0x7ff8000000000000LL);       // compares false: contributes nothing
+    for (int v0 = lane; v0 < nW; v0 += 256) {
+        double sv[4];
 #pragma unroll
-        for (int q = 0; q < Q; ++q) {
-            const bool ahead = reverse ? (sv < sw[q]) : (sv > sw[q]);
-            rank[q] += (ahead || (sv == sw[q] && v < w0 + q)) ? 1 : 0;
+        for (int u = 0; u < 4; ++u) { const int v = v0 + 64 * u; sv[u] = v < nW ? rsc[v] : nan; }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int v = v0 + 64 * u;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const bool ahead = reverse ? (sv[u] < sw[q]) : (sv[u] > sw[q]);
+                rank[q] += (ahead || (sv[u] == sw[q] && v < w0 + q)) ? 1 : 0;
+            }
         }
     }
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) rank[q] += __shfl_xor(rank[q], o, 64);
-        if (lane == 0 && w0 + q < nW) perm[(size_t)b * nW + w0 + q] = rank[q] < k_hi ? 0 : (rank[q] < k_hi + k_lo ? 1 : 2);
-    }
-}
-
-__global__ __launch_bounds__(1024) void select_place_kernel(int nW, int k_hi, int k_lo, int* __restrict__ perm)
-{
-    extern __shared__ int smi[];
-    int* grp = smi;                                   // [nW] group of every window: 0 high, 1 low, 2 pruned
-    int* wsum = smi + nW;                             // [16] per-wave totals, (high << 16) | low
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int i = tid; i < nW; i += 1024) grp[i] = perm[(size_t)b * nW + i];
-    __syncthreads();
-    const int chunk = (nW + 1023) / 1024;
-    const int lo = min(tid * chunk, nW), hi = min(lo + chunk, nW);
-    int cnt = 0;
-    for (int i = lo; i < hi; ++i) cnt += grp[i] == 0 ? 0x10000 : (grp[i] == 1 ? 1 : 0);
-    int incl = cnt;                                   // inclusive scan inside the wave
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) { int t = __shfl_up(incl, o, 64); if (lane >= o) incl += t; }
-    if (lane == 63) wsum[wave] = incl;
-    __syncthreads();
-    int before = 0;
-    for (int k = 0; k < wave; ++k) before += wsum[k];
-    const int ex = before + incl - cnt;
-    int nh = ex >> 16, nl = ex & 0xffff;              // high / low windows before this chunk
-    for (int i = lo; i < hi; ++i) {
-        const int np = i - nh - nl;                   // pruned windows before i
-        const int g = grp[i];
-        if (g == 0) perm[(size_t)b * nW + nh++] = i;
-        else if (g == 1) perm[(size_t)b * nW + k_hi + nl++] = i;
-        else perm[(size_t)b * nW + k_hi + k_lo + np] = i;
+        if (lane == 0 && w0 + q < nW) perm[(size_t)b * nW + rank[q]] = w0 + q;
     }
 }
 
@@ -333,15 +316,12 @@ __device__ __forceinline__ void attention_core(const v4i (&qf)[2], const v4i (&k
                                                const AttnCore& A, int j, int g, v16i (&o)[2])
 {
     const v16i zero16 = {0};
-    v16i s[2][2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int ib = 0; ib < 2; ++ib) s[kb][ib] = mfma32(kf[kb], qf[ib], zero16);
-    v4i pk[2][2];
 #pragma unroll
     for (int ib = 0; ib < 2; ++ib) {
         const int qi = ib * 32 + j;                                       // this lane's query
+        v16i s[2];                                                        // S^T tiles of this query block, per key block
+        s[0] = mfma32(kf[0], qf[ib], zero16);
+        s[1] = mfma32(kf[1], qf[ib], zero16);
         float lg[2][16];
         float mx = -INFINITY;
 #pragma unroll
@@ -352,8 +332,9 @@ __device__ __forceinline__ void attention_core(const v4i (&qf)[2], const v4i (&k
                 float v = -INFINITY;
                 if (key < TOK) {                                          // valid for at least one half
                     const int kk = key + g * 4;
-                    if (kk < TOK) v = fmaf((float)s[kb][ib][r], A.m2, A.bm[kk * 64 + qi]);
+                    if (kk < TOK) v = fmaf((float)s[kb][r], A.m2, A.bm[kk * 64 + qi]);
                     mx = fmaxf(mx, v);
+                    if (TAPS && kk < TOK && qi < TOK && A.tap_s) A.tap_s[qi * TOK + kk] = s[kb][r];
                 }
                 lg[kb][r] = v;
             }
@@ -373,6 +354,7 @@ __device__ __forceinline__ void attention_core(const v4i (&qf)[2], const v4i (&k
             }
         den += __shfl_xor(den, 32, 64);
         const float rden = 1.0f / (float)den;
+        v4i pk[2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             int wd[4];
@@ -387,22 +369,16 @@ __device__ __forceinline__ void attention_core(const v4i (&qf)[2], const v4i (&k
                         const int kk = key + g * 4;
                         if (kk < TOK) {
                             c[e] = quant_code(lg[kb][r] * rden, A.qp);
-                            if (TAPS && qi < TOK) {
-                                if (A.tap_s) A.tap_s[qi * TOK + kk] = s[kb][ib][r];
-                                if (A.tap_p) A.tap_p[qi * TOK + kk] = (int8_t)c[e];
-                            }
+                            if (TAPS && qi < TOK && A.tap_p) A.tap_p[qi * TOK + kk] = (int8_t)c[e];
                         }
                     }
                 }
                 wd[qd] = pack4(c[0], c[1], c[2], c[3]);
             }
-            pk[kb][ib] = (v4i){wd[0], wd[1], wd[2], wd[3]};
+            pk[kb] = (v4i){wd[0], wd[1], wd[2], wd[3]};
         }
-    }
-#pragma unroll
-    for (int ib = 0; ib < 2; ++ib) {
-        o[ib] = mfma32(vt[0], pk[0][ib], zero16);
-        o[ib] = mfma32(vt[1], pk[1][ib], o[ib]);
+        o[ib] = mfma32(vt[0], pk[0], zero16);
+        o[ib] = mfma32(vt[1], pk[1], o[ib]);
     }
 }
 
@@ -517,7 +493,7 @@ __global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
 //   fragments -> per head: q, k (transposed product, lane = token) and v (plain product, lane =
 //   dim) straight into operand registers -> attention core -> codes of the attention output.
 #ifndef WIN_WAVES_PER_EU
-#define WIN_WAVES_PER_EU 3
+#define WIN_WAVES_PER_EU 2
 #endif
 template <int NH>
 struct WinCfg {
@@ -571,9 +547,6 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
         }
     }
     __syncthreads();
-#ifdef MIXAQ_PRIO
-    __builtin_amdgcn_s_setprio(1);
-#endif
     const int head = wave;
     v4i bf[2][KS];
 #pragma unroll
@@ -660,9 +633,6 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
         cs += __shfl_xor(cs, 32, 64);
         if (g == 0) csum[wave][j] = cs;
     }
-#ifdef MIXAQ_PRIO
-    __builtin_amdgcn_s_setprio(2);
-#endif
     AttnCore core;
     core.poly = &A.poly;
     core.bm = A.bias2 + ((size_t)(mask_type(G, w) * NH + head) * TOK) * 64;
@@ -683,47 +653,79 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
 //   proj + first residual (wave w owns channels 32w..32w+31, h stays in registers) -> LN2 with
 //   statistics exchanged through LDS -> quantize -> FC1 (each wave 4 hidden blocks) + GELU +
 //   quantize, codes to LDS as fragments -> FC2 + second residual -> scatter to the map.
+// Latency is hidden by issuing loads a phase ahead: the per-branch parameter block (epilogue
+// constants, LN2 affine) is staged in LDS once, weight fragments of the next MFMA chain are
+// requested before the current epilogue starts.
 #ifndef TOK_WAVES_PER_EU
 #define TOK_WAVES_PER_EU 4
 #endif
+// word offsets inside the parameter block of one branch (see TokArgs::params)
+template <int C> struct TokPrm {
+    static constexpr int F = 4 * C;
+    static constexpr int P_M = 0, P_B = C, P_NC = 2 * C, LN_G = 3 * C, LN_B = 4 * C, F2_M = 5 * C, F2_B = 6 * C,
+                         F2_NC = 7 * C, F1_M = 8 * C, F1_B = 8 * C + F, F1_NC = 8 * C + 2 * F, WORDS = 8 * C + 3 * F;
+};
+
 template <int NH, bool TAPS>
-__global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(TOK_WAVES_PER_EU))) void token_kernel(Geom G, TokArgs A)
+__global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(TOK_WAVES_PER_EU, TOK_WAVES_PER_EU))) void token_kernel(Geom G, TokArgs A)
 {
-    constexpr int C = NH * 32, KS = NH, HB = 4 * NH, F = 4 * C;
+    constexpr int C = NH * 32, KS = NH, HB = 4 * NH, F = 4 * C, NT = NH * 64;
+    using PR = TokPrm<C>;
+    constexpr int PV = PR::WORDS / 4, PVT = (PV + NT - 1) / NT;       // float4 of the block, per thread
+    constexpr int D2 = 4;                                            // FC2 weight fragments in flight
     __shared__ v4i a2s[KS * 64];
     __shared__ v4i gs[HB * 64];
     __shared__ double part[2][NH][32];
+    __shared__ __attribute__((aligned(16))) float prm[PR::WORDS];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, g = lane >> 5;
     const int row = blockIdx.x * 32 + j;
     const int branch = row >= G.base_lo ? 1 : 0;
     const bool valid = branch ? (row - G.base_lo < G.rows_lo) : (row < G.rows_hi);
-    const int pix = valid ? A.row_pix[row] : -1;
-    const size_t canon = valid ? (size_t)A.row_canon[row] : 0;
-    const bool tap_ok = TAPS && valid;
     const int nb = wave;
+    // ---- loads that depend on nothing: parameter block, attention codes, first weight fragments
+    float4 pv[PVT];
+    {
+        const float4* psrc = (const float4*)A.params[branch];
+#pragma unroll
+        for (int k = 0; k < PVT; ++k) { const int idx = tid + k * NT; if (idx < PV) pv[k] = psrc[idx]; }
+    }
+    const int pix = valid ? A.row_pix[row] : -1;
+    const size_t canon = (TAPS && valid) ? (size_t)A.row_canon[row] : 0;
+    const bool tap_ok = TAPS && valid;
+    v4i aof[KS], wpf[KS], w1f[KS];
+    {
+        const int8_t* ap = A.ao + (size_t)row * C + g * 16;
+        const v4i* wp = A.Wproj + (size_t)nb * KS * 64 + lane;
+        const v4i* w1 = A.W1 + (size_t)wave * KS * 64 + lane;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) { aof[ks] = *(const v4i*)(ap + ks * 32); wpf[ks] = wp[ks * 64]; w1f[ks] = w1[ks * 64]; }
+    }
+#pragma unroll
+    for (int k = 0; k < PVT; ++k) { const int idx = tid + k * NT; if (idx < PV) ((float4*)prm)[idx] = pv[k]; }
+    float4 sc[4];
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd)
+        sc[qd] = pix >= 0 ? *(const float4*)(A.x + (size_t)pix * C + nb * 32 + qd * 8 + g * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();                                                  // parameter block visible
+    const int* prmi = (const int*)prm;
     float h[16];
     {   // output projection + first residual
         v16i acc;
-        const int* nc = A.p_negcorr[branch] + nb * 32 + g * 4;
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
-            int4 t4 = *(const int4*)(nc + qd * 8);
+            const int4 t4 = *(const int4*)(prmi + PR::P_NC + nb * 32 + qd * 8 + g * 4);
             acc[qd * 4 + 0] = t4.x; acc[qd * 4 + 1] = t4.y; acc[qd * 4 + 2] = t4.z; acc[qd * 4 + 3] = t4.w;
         }
-        const int8_t* ap = A.ao + (size_t)row * C + g * 16;
-        const v4i* wp = A.Wproj + (size_t)nb * KS * 64 + lane;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) acc = mfma32(wp[ks * 64], *(const v4i*)(ap + ks * 32), acc);
+        for (int ks = 0; ks < KS; ++ks) acc = mfma32(wpf[ks], aof[ks], acc);
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
             const int n0 = nb * 32 + qd * 8 + g * 4;
-            const float4 m = *(const float4*)(A.p_m[branch] + n0), bs = *(const float4*)(A.p_bias[branch] + n0);
-            float4 sc = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (pix >= 0) sc = *(const float4*)(A.x + (size_t)pix * C + n0);
-            h[qd * 4 + 0] = fmaf((float)acc[qd * 4 + 0], m.x, bs.x) + sc.x;
-            h[qd * 4 + 1] = fmaf((float)acc[qd * 4 + 1], m.y, bs.y) + sc.y;
-            h[qd * 4 + 2] = fmaf((float)acc[qd * 4 + 2], m.z, bs.z) + sc.z;
-            h[qd * 4 + 3] = fmaf((float)acc[qd * 4 + 3], m.w, bs.w) + sc.w;
+            const float4 m = *(const float4*)(prm + PR::P_M + n0), bs = *(const float4*)(prm + PR::P_B + n0);
+            h[qd * 4 + 0] = fmaf((float)acc[qd * 4 + 0], m.x, bs.x) + sc[qd].x;
+            h[qd * 4 + 1] = fmaf((float)acc[qd * 4 + 1], m.y, bs.y) + sc[qd].y;
+            h[qd * 4 + 2] = fmaf((float)acc[qd * 4 + 2], m.z, bs.z) + sc[qd].z;
+            h[qd * 4 + 3] = fmaf((float)acc[qd * 4 + 3], m.w, bs.w) + sc[qd].w;
             if (tap_ok) {
                 if (A.tap_acc_proj) *(int4*)(A.tap_acc_proj + canon * C + n0) = make_int4(acc[qd * 4], acc[qd * 4 + 1], acc[qd * 4 + 2], acc[qd * 4 + 3]);
                 if (A.tap_h) *(float4*)(A.tap_h + canon * C + n0) = make_float4(h[qd * 4], h[qd * 4 + 1], h[qd * 4 + 2], h[qd * 4 + 3]);
@@ -761,7 +763,7 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(TOK_WAV
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
             const int n0 = nb * 32 + qd * 8 + g * 4;
-            const float4 gm = *(const float4*)(A.gamma[branch] + n0), bt = *(const float4*)(A.beta[branch] + n0);
+            const float4 gm = *(const float4*)(prm + PR::LN_G + n0), bt = *(const float4*)(prm + PR::LN_B + n0);
             wd[qd] = pack4(quant_code(fmaf((h[qd * 4 + 0] - mean) * rstd, gm.x, bt.x), qa),
                            quant_code(fmaf((h[qd * 4 + 1] - mean) * rstd, gm.y, bt.y), qa),
                            quant_code(fmaf((h[qd * 4 + 2] - mean) * rstd, gm.z, bt.z), qa),
@@ -771,9 +773,8 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(TOK_WAV
         a2s[nb * 64 + lane] = (v4i){wd[0], wd[1], wd[2], wd[3]};       // k slab nb, byte r = channel 32nb + mfma_row(r,g)
     }
     __syncthreads();
-#ifdef MIXAQ_PRIO
-    __builtin_amdgcn_s_setprio(1);
-#endif
+    v4i w2q[D2];                                                      // first FC2 weight fragments, requested during FC1
+    const v4i* w2p = A.W2 + (size_t)nb * HB * 64 + lane;
     {   // FC1 + GELU + quantize for hidden blocks wave, wave+NH, ...
         v4i af[KS];
 #pragma unroll
@@ -783,20 +784,26 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(TOK_WAV
         for (int i = 0; i < 4; ++i) {
             const int hb = wave + NH * i;
             v16i acc;
-            const int* nc = A.f1_negcorr[branch] + hb * 32 + g * 4;
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
-                int4 t4 = *(const int4*)(nc + qd * 8);
+                const int4 t4 = *(const int4*)(prmi + PR::F1_NC + hb * 32 + qd * 8 + g * 4);
                 acc[qd * 4 + 0] = t4.x; acc[qd * 4 + 1] = t4.y; acc[qd * 4 + 2] = t4.z; acc[qd * 4 + 3] = t4.w;
             }
-            const v4i* wp = A.W1 + (size_t)hb * KS * 64 + lane;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) acc = mfma32(wp[ks * 64], af[ks], acc);
+            for (int ks = 0; ks < KS; ++ks) acc = mfma32(w1f[ks], af[ks], acc);
+            if (i < 3) {                                              // weights of the next hidden block
+                const v4i* w1 = A.W1 + (size_t)(hb + NH) * KS * 64 + lane;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) w1f[ks] = w1[ks * 64];
+            } else {
+#pragma unroll
+                for (int d = 0; d < D2; ++d) w2q[d] = w2p[d * 64];
+            }
             int wd[4];
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 const int n0 = hb * 32 + qd * 8 + g * 4;
-                const float4 m = *(const float4*)(A.f1_m[branch] + n0), bs = *(const float4*)(A.f1_bias[branch] + n0);
+                const float4 m = *(const float4*)(prm + PR::F1_M + n0), bs = *(const float4*)(prm + PR::F1_B + n0);
                 wd[qd] = pack4(quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 0], m.x, bs.x), A.poly), qg),
                                quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 1], m.y, bs.y), A.poly), qg),
                                quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 2], m.z, bs.z), A.poly), qg),
@@ -807,30 +814,26 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(TOK_WAV
                 }
             }
             gs[hb * 64 + lane] = (v4i){wd[0], wd[1], wd[2], wd[3]};
-#ifdef MIXAQ_PRIO
-            if (i == 1) __builtin_amdgcn_s_setprio(2);
-#endif
         }
     }
-#ifdef MIXAQ_PRIO
-    __builtin_amdgcn_s_setprio(3);
-#endif
     __syncthreads();
     {   // FC2 + second residual + scatter
         v16i acc;
-        const int* nc = A.f2_negcorr[branch] + nb * 32 + g * 4;
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
-            int4 t4 = *(const int4*)(nc + qd * 8);
+            const int4 t4 = *(const int4*)(prmi + PR::F2_NC + nb * 32 + qd * 8 + g * 4);
             acc[qd * 4 + 0] = t4.x; acc[qd * 4 + 1] = t4.y; acc[qd * 4 + 2] = t4.z; acc[qd * 4 + 3] = t4.w;
         }
-        const v4i* wp = A.W2 + (size_t)nb * HB * 64 + lane;
-#pragma unroll 4
-        for (int hb = 0; hb < HB; ++hb) acc = mfma32(wp[hb * 64], gs[hb * 64 + lane], acc);
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) {
+            const v4i w = w2q[hb % D2];
+            if (hb + D2 < HB) w2q[hb % D2] = w2p[(hb + D2) * 64];
+            acc = mfma32(w, gs[hb * 64 + lane], acc);
+        }
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
             const int n0 = nb * 32 + qd * 8 + g * 4;
-            const float4 m = *(const float4*)(A.f2_m[branch] + n0), bs = *(const float4*)(A.f2_bias[branch] + n0);
+            const float4 m = *(const float4*)(prm + PR::F2_M + n0), bs = *(const float4*)(prm + PR::F2_B + n0);
             float4 o4 = make_float4(fmaf((float)acc[qd * 4 + 0], m.x, bs.x) + h[qd * 4 + 0], fmaf((float)acc[qd * 4 + 1], m.y, bs.y) + h[qd * 4 + 1],
                                     fmaf((float)acc[qd * 4 + 2], m.z, bs.z) + h[qd * 4 + 2], fmaf((float)acc[qd * 4 + 3], m.w, bs.w) + h[qd * 4 + 3]);
             if (pix >= 0) *(float4*)(A.y + (size_t)pix * C + n0) = o4;
@@ -892,11 +895,10 @@ void launch_bypass(const Geom& G, const int* perm, const float* x, float* y, hip
     if (n_pruned > 0) hipLaunchKernelGGL(bypass_kernel, dim3(G.B * n_pruned), dim3(256), 0, st, G, perm, x, y);
 }
 
-void launch_select(const double* scores, int B, int nW, int k_hi, int k_lo, int reverse, int* perm, hipStream_t st)
+void launch_select(const double* scores, int B, int nW, int reverse, int* perm, hipStream_t st)
 {
-    hipLaunchKernelGGL(select_rank_kernel, dim3((nW + RANK_WPB - 1) / RANK_WPB, B), dim3(256), (size_t)nW * 8, st, scores, nW, k_hi,
-                       k_lo, reverse, perm);
-    hipLaunchKernelGGL(select_place_kernel, dim3(B), dim3(1024), (size_t)nW * 4 + 64, st, nW, k_hi, k_lo, perm);
+    hipLaunchKernelGGL(select_rank_kernel, dim3((nW + RANK_WPB - 1) / RANK_WPB, B), dim3(256), (size_t)nW * 8, st, scores, nW, reverse,
+                       perm);
 }
 
 bool launch_ln_quant(const Geom& G, const LnArgs& A, bool gather, hipStream_t st)

@@ -197,9 +197,11 @@ def test_selection_against_sort():
             for b in range(3):
                 key = sc[b] if reverse else -sc[b]
                 order = np.lexsort((np.arange(nW), key))          # (score desc, index asc)
-                assert np.array_equal(perm[b, :k], np.sort(order[:k]))
-                assert np.array_equal(perm[b, k:], np.sort(order[k:]))
+                assert np.array_equal(perm[b], order)
                 assert np.array_equal(np.sort(perm[b]), np.arange(nW))
+                if k and k < nW:                                  # every high score >= every low score
+                    hi, lo = sc[b][perm[b, :k]], sc[b][perm[b, k:]]
+                    assert (hi.min() <= lo.max()) if reverse else (hi.min() >= lo.max())
 
 
 # ---------------------------------------------------------------- whole block
@@ -402,9 +404,7 @@ def test_pruned_windows_are_forwarded_and_the_rest_unchanged():
     perm3 = O.select_windows(sc, kh, k_low=kl)
     for b in range(2):
         order = np.lexsort((np.arange(nW), -sc[b]))
-        assert np.array_equal(perm3[b, :kh], np.sort(order[:kh]))
-        assert np.array_equal(perm3[b, kh:kh + kl], np.sort(order[kh:kh + kl]))
-        assert np.array_equal(perm3[b, kh + kl:], np.sort(order[kh + kl:]))
+        assert np.array_equal(perm3[b], order)
     y3, _ = O.block_forward(inp, x, perm3, kh, k_low=kl)
     # same high group, every other window low: the un-pruned reference
     perm2 = perm3.copy()
