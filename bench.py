@@ -3,8 +3,9 @@
 
 One step = one pass of the whole path over the Swin-T stage-1 pair at detection
 scale (BASELINE config 2): score the 1392 windows of a 200x336x96 map once,
-select the high group (keep ratio 0.5), run the regular block and then the
-shifted block (A8 high / A4 low, int8 per-channel weights).  Inputs are seeded
+run the regular block and then the shifted block (A8 high / A4 low, int8
+per-channel weights); the first kernel of each block takes the selection (keep
+ratio 0.5) from the scores.  Inputs are seeded
 synthetic tensors already resident in HBM; block creation (weight packing) is
 outside the timed region.  Prints ONE JSON line.
 """
@@ -105,11 +106,15 @@ def main():
     bufs = [torch.empty_like(x), torch.empty_like(x)]
 
     def step():
+        # score once for the stage; the first block takes the selection from the scores inside its first
+        # kernel and hands the list to the stage's other blocks
         M.mixaq_score_windows(blocks[0], x, scores)
-        M.mixaq_select_windows(scores, spec.B, spec.nW, k_high, 0, perm)
         cur = x
         for i, blk in enumerate(blocks):
-            M.mixaq_block_forward(blk, cur, perm, k_high, bufs[i % 2], ws)
+            if i == 0:
+                M.mixaq_block_forward_scored(blk, cur, scores, k_high, -1, bufs[i % 2], ws, perm_out=perm)
+            else:
+                M.mixaq_block_forward(blk, cur, perm, k_high, bufs[i % 2], ws)
             cur = bufs[i % 2]
         return cur
 
@@ -137,16 +142,12 @@ def main():
         ev1.synchronize()
         acc["score"] += ev0.elapsed_time(ev1) / REP
         launches["score"] += 1
-        ev0.record()
-        for _r in range(REP):
-            M.mixaq_select_windows(scores, spec.B, spec.nW, k_high, 0, perm)
-        ev1.record()
-        ev1.synchronize()
-        acc["select"] += ev0.elapsed_time(ev1) / REP
-        launches["select"] += 1
         cur = x
         for i, blk in enumerate(blocks):
-            ms = M.mixaq_block_forward_profile(blk, cur, perm, k_high, bufs[i % 2], ws, repeats=4)
+            if i == 0:
+                ms = M.mixaq_block_forward_profile(blk, cur, None, k_high, bufs[i % 2], ws, repeats=REP, scores=scores)
+            else:
+                ms = M.mixaq_block_forward_profile(blk, cur, perm, k_high, bufs[i % 2], ws, repeats=REP)
             cur = bufs[i % 2]
             for n, v in ms.items():
                 if v > 0:

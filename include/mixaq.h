@@ -156,6 +156,15 @@ int mixaq_block_forward(const mixaq_block *blk, const float *x, const int32_t *p
  * and selects internally with the same three-way split. */
 int mixaq_block_forward_pruned(const mixaq_block *blk, const float *x, const int32_t *perm, int32_t k_high,
                                int32_t k_low, float *y, void *workspace, size_t workspace_bytes, void *stream);
+/* The block given the SCORES instead of a selection list (scores: device double [B,nW] from
+ * mixaq_score_windows, shared by the blocks of a stage): the selection of Sec. 3.2 / 3.4 is taken
+ * inside the first kernel, where every window finds its own rank.  Same result as
+ * mixaq_select_windows3 followed by mixaq_block_forward_pruned; k_low < 0 means no pruning
+ * (k_low = nW - k_high).  perm_out (device int32 [B,nW], may be NULL) receives the selection
+ * list, for the later blocks of the stage. */
+int mixaq_block_forward_scored(const mixaq_block *blk, const float *x, const double *scores, int32_t k_high,
+                               int32_t k_low, float *y, int32_t *perm_out, void *workspace, size_t workspace_bytes,
+                               void *stream);
 /* Same as mixaq_block_forward, and also fills the given taps. */
 int mixaq_block_forward_taps(const mixaq_block *blk, const float *x, const int32_t *perm, int32_t k_high,
                              float *y, void *workspace, size_t workspace_bytes, void *stream,
@@ -197,10 +206,11 @@ int mixaq_block_set_fused(mixaq_block *blk, int32_t enable);
  * recomputes the same result) between two HIP events on `stream`; synchronises
  * the stream and writes the mean duration of each kernel in milliseconds to the
  * HOST array kernel_ms[MIXAQ_NUM_KERNELS] (0 for kernels that did not run, e.g.
- * score and select when perm is given).  mixaq_kernel_name(i) names entry i. */
+ * score and select when perm is given).  perm / scores as in mixaq_block_forward /
+ * mixaq_block_forward_scored (at most one non-NULL).  mixaq_kernel_name(i) names entry i. */
 #define MIXAQ_NUM_KERNELS 11
-int mixaq_block_forward_profile(const mixaq_block *blk, const float *x, const int32_t *perm, int32_t k_high,
-                                float *y, void *workspace, size_t workspace_bytes, void *stream,
+int mixaq_block_forward_profile(const mixaq_block *blk, const float *x, const int32_t *perm, const double *scores,
+                                int32_t k_high, float *y, void *workspace, size_t workspace_bytes, void *stream,
                                 int32_t repeats, float *kernel_ms);
 const char *mixaq_kernel_name(int32_t i);
 

@@ -77,7 +77,10 @@ def load():
                                             C.c_void_p]
         L.mixaq_block_forward_pruned.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                                  C.c_void_p, C.c_size_t, C.c_void_p]
-        L.mixaq_block_forward_profile.argtypes = L.mixaq_block_forward.argtypes + [C.c_int32, C.POINTER(C.c_float)]
+        L.mixaq_block_forward_profile.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                                  C.c_void_p, C.c_size_t, C.c_void_p, C.c_int32, C.POINTER(C.c_float)]
+        L.mixaq_block_forward_scored.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                                 C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.mixaq_block_set_fused.argtypes = [C.c_void_p, C.c_int32]
         L.mixaq_kernel_name.restype = C.c_char_p
         L.mixaq_kernel_name.argtypes = [C.c_int32]
@@ -229,11 +232,17 @@ def mixaq_kernel_name(i):
     return load().mixaq_kernel_name(i).decode()
 
 
-def mixaq_block_forward_profile(blk, x, perm, k_high, y, workspace, repeats=1, stream=None):
+def mixaq_block_forward_scored(blk, x, scores, k_high, k_low, y, workspace, perm_out=None, stream=None):
+    _check(load().mixaq_block_forward_scored(blk, _ptr(x), _ptr(scores), k_high, k_low, _ptr(y), _ptr(perm_out), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream(stream)))
+    return y
+
+
+def mixaq_block_forward_profile(blk, x, perm, k_high, y, workspace, repeats=1, stream=None, scores=None):
     """One forward with HIP events around every kernel (each launched `repeats` times);
     returns {kernel name: mean milliseconds}."""
     ms = (C.c_float * NUM_KERNELS)()
-    _check(load().mixaq_block_forward_profile(blk, _ptr(x), _ptr(perm), k_high, _ptr(y), _ptr(workspace),
+    _check(load().mixaq_block_forward_profile(blk, _ptr(x), _ptr(perm), _ptr(scores), k_high, _ptr(y), _ptr(workspace),
                                               workspace.numel() * workspace.element_size(), _stream(stream), int(repeats), ms))
     return {mixaq_kernel_name(i): float(ms[i]) for i in range(NUM_KERNELS)}
 

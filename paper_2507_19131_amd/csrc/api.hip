@@ -241,8 +241,9 @@ struct Prof {
     int repeats = 1;          // every kernel is launched this many times between its two events
 };
 
-int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, int32_t k_low, float* y,
-                 void* workspace, size_t workspace_bytes, void* stream, const mixaq_taps* taps, Prof* prof = nullptr)
+int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, const double* scores, int32_t k_high,
+                 int32_t k_low, float* y, void* workspace, size_t workspace_bytes, void* stream, const mixaq_taps* taps,
+                 Prof* prof = nullptr, int32_t* perm_out = nullptr)
 {
     if (!blk) return fail(MIXAQ_E_NULL, "block is NULL");
     if (!x || !y) return fail(MIXAQ_E_NULL, "x or y is NULL");
@@ -270,17 +271,23 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, in
     auto mark = [&](int kernel) {
         if (prof) { prof->idx[prof->n] = kernel; (void)hipEventRecord(prof->ev[prof->n++], st); }
     };
-    if (!perm) {     // score and select here (single-block use)
+    if (!perm && !scores) {     // score here (single-block use)
         mark(0);
         for (int r = 0; r < reps; ++r) launch_score(G, x, d.score_mode, d.ln_eps, blk->score_gamma, blk->score_beta, ws.scores, st);
-        mark(1);
-        for (int r = 0; r < reps; ++r) launch_select(ws.scores, d.B, blk->nW, 0, ws.perm, st);
-        perm = ws.perm;
+        scores = ws.scores;
     }
-    launch_bypass(G, perm, x, y, st);                // pruned windows (if any) are forwarded
+    // the fused window kernel ranks the windows itself when it is given scores; the other path selects first
+    const bool in_kernel_select = !perm && blk->fused;
+    if (!perm && !in_kernel_select) {
+        mark(1);
+        for (int r = 0; r < reps; ++r) launch_select(scores, d.B, blk->nW, 0, perm_out ? perm_out : ws.perm, st);
+        perm = perm_out ? perm_out : ws.perm;
+    }
+    if (!in_kernel_select) launch_bypass(G, perm, x, y, st);       // pruned windows (if any) are forwarded
     if (blk->fused) {
         WinArgs wa = {};
-        wa.x = x; wa.perm = perm; wa.eps = d.ln_eps; wa.Wqkv = blk->qkv.Wp; wa.bias2 = blk->bias2; wa.out = ws.ao;
+        wa.x = x; wa.perm = perm; wa.scores = in_kernel_select ? scores : nullptr; wa.reverse = 0; wa.perm_out = perm_out ? perm_out : ws.perm;
+        wa.y = y; wa.eps = d.ln_eps; wa.Wqkv = blk->qkv.Wp; wa.bias2 = blk->bias2; wa.out = ws.ao;
         wa.row_pix = ws.row_pix; wa.row_canon = ws.row_canon;
         TokArgs ta = {};
         ta.ao = ws.ao; ta.x = x; ta.y = y; ta.row_pix = ws.row_pix; ta.row_canon = ws.row_canon; ta.eps = d.ln_eps;
@@ -547,20 +554,28 @@ int mixaq_select_windows(const double* scores, int32_t B, int32_t nW, int32_t k_
 int mixaq_block_forward(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, float* y,
                         void* workspace, size_t workspace_bytes, void* stream)
 {
-    return forward_impl(blk, x, perm, k_high, -1, y, workspace, workspace_bytes, stream, nullptr);
+    return forward_impl(blk, x, perm, nullptr, k_high, -1, y, workspace, workspace_bytes, stream, nullptr);
+}
+
+int mixaq_block_forward_scored(const mixaq_block* blk, const float* x, const double* scores, int32_t k_high, int32_t k_low,
+                               float* y, int32_t* perm_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!scores) return fail(MIXAQ_E_NULL, "scores is NULL");
+    return forward_impl(blk, x, nullptr, scores, k_high, k_low, y, workspace, workspace_bytes, stream, nullptr, nullptr,
+                        perm_out);
 }
 
 int mixaq_block_forward_pruned(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, int32_t k_low,
                                float* y, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (k_low < 0) return fail(MIXAQ_E_SHAPE, "k_low must not be negative");
-    return forward_impl(blk, x, perm, k_high, k_low, y, workspace, workspace_bytes, stream, nullptr);
+    return forward_impl(blk, x, perm, nullptr, k_high, k_low, y, workspace, workspace_bytes, stream, nullptr);
 }
 
 int mixaq_block_forward_taps(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, float* y,
                              void* workspace, size_t workspace_bytes, void* stream, const mixaq_taps* taps)
 {
-    return forward_impl(blk, x, perm, k_high, -1, y, workspace, workspace_bytes, stream, taps);
+    return forward_impl(blk, x, perm, nullptr, k_high, -1, y, workspace, workspace_bytes, stream, taps);
 }
 
 int mixaq_block_set_fused(mixaq_block* blk, int32_t enable)
@@ -580,14 +595,15 @@ const char* mixaq_kernel_name(int32_t i)
     return (i >= 0 && i < MIXAQ_NUM_KERNELS) ? names[i] : "";
 }
 
-int mixaq_block_forward_profile(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, float* y,
-                                void* workspace, size_t workspace_bytes, void* stream, int32_t repeats, float* kernel_ms)
+int mixaq_block_forward_profile(const mixaq_block* blk, const float* x, const int32_t* perm, const double* scores,
+                                int32_t k_high, float* y, void* workspace, size_t workspace_bytes, void* stream,
+                                int32_t repeats, float* kernel_ms)
 {
     if (!kernel_ms) return fail(MIXAQ_E_NULL, "kernel_ms is NULL");
     Prof prof;
     for (int i = 0; i <= MIXAQ_NUM_KERNELS; ++i) HIP_TRY(hipEventCreate(&prof.ev[i]));
     prof.repeats = repeats < 1 ? 1 : repeats;
-    int rc = forward_impl(blk, x, perm, k_high, -1, y, workspace, workspace_bytes, stream, nullptr, &prof);
+    int rc = forward_impl(blk, x, perm, scores, k_high, -1, y, workspace, workspace_bytes, stream, nullptr, &prof);
     if (rc == MIXAQ_OK && hipStreamSynchronize((hipStream_t)stream) != hipSuccess) rc = fail(MIXAQ_E_HIP, "stream synchronisation failed");
     for (int i = 0; i < MIXAQ_NUM_KERNELS; ++i) kernel_ms[i] = 0.0f;
     if (rc == MIXAQ_OK)

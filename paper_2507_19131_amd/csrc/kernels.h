@@ -68,7 +68,11 @@ struct AttnArgs {
 
 struct WinArgs {                     // fused window kernel (gather + LN1 + QKV + attention)
     const float* x;
-    const int* perm;
+    const int* perm;                 // selection list, or ...
+    const double* scores;            // ... the scores: every workgroup ranks its own window ([B,nW]; NULL = use perm)
+    int reverse;                     // with scores: invert the order of importance
+    int* perm_out;                   // with scores: receives the selection list
+    float* y;                        // with scores: pruned windows are forwarded here
     const float* gamma[2];
     const float* beta[2];
     float eps;

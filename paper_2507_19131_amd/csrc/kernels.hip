@@ -24,14 +24,13 @@ __device__ __forceinline__ double group_sum(double v)
 // element e of vector k on lane i: (k*LPT + i)*4 + e).  Mean and variance in
 // binary64, rounded once.
 template <int LPT, int NV>
-__device__ __forceinline__ void token_layernorm(float4 (&v)[NV], int C, float eps, const float* __restrict__ gamma,
-                                                const float* __restrict__ beta, int sub)
+__device__ __forceinline__ void token_ln_stats(const float4 (&v)[NV], int C, float eps, float& mean, float& rstd)
 {
     double s = 0.0;
 #pragma unroll
     for (int k = 0; k < NV; ++k) s += ((double)v[k].x + (double)v[k].y) + ((double)v[k].z + (double)v[k].w);
     s = group_sum<LPT>(s);
-    float mean = (float)(s / (double)C);
+    mean = (float)(s / (double)C);
     double q = 0.0;
 #pragma unroll
     for (int k = 0; k < NV; ++k) {
@@ -40,8 +39,14 @@ __device__ __forceinline__ void token_layernorm(float4 (&v)[NV], int C, float ep
         q += (a * a + b * b) + (c * c + d * d);
     }
     q = group_sum<LPT>(q);
-    float var = (float)(q / (double)C);
-    float rstd = 1.0f / sqrtf(var + eps);
+    const float var = (float)(q / (double)C);
+    rstd = 1.0f / sqrtf(var + eps);
+}
+
+template <int LPT, int NV>
+__device__ __forceinline__ void token_ln_apply(float4 (&v)[NV], float mean, float rstd, const float* __restrict__ gamma,
+                                               const float* __restrict__ beta, int sub)
+{
 #pragma unroll
     for (int k = 0; k < NV; ++k) {
         int ch = (k * LPT + sub) * 4;
@@ -51,6 +56,15 @@ __device__ __forceinline__ void token_layernorm(float4 (&v)[NV], int C, float ep
         v[k].z = fmaf((v[k].z - mean) * rstd, g.z, b.z);
         v[k].w = fmaf((v[k].w - mean) * rstd, g.w, b.w);
     }
+}
+
+template <int LPT, int NV>
+__device__ __forceinline__ void token_layernorm(float4 (&v)[NV], int C, float eps, const float* __restrict__ gamma,
+                                                const float* __restrict__ beta, int sub)
+{
+    float mean, rstd;
+    token_ln_stats<LPT, NV>(v, C, eps, mean, rstd);
+    token_ln_apply<LPT, NV>(v, mean, rstd, gamma, beta, sub);
 }
 
 // ------------------------------------------------------------------ K0 score
@@ -493,7 +507,7 @@ __global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
 //   fragments -> per head: q, k (transposed product, lane = token) and v (plain product, lane =
 //   dim) straight into operand registers -> attention core -> codes of the attention output.
 #ifndef WIN_WAVES_PER_EU
-#define WIN_WAVES_PER_EU 2
+#define WIN_WAVES_PER_EU 3
 #endif
 template <int NH>
 struct WinCfg {
@@ -501,49 +515,96 @@ struct WinCfg {
     static constexpr int NV = NH * 32 / (4 * LPT);
 };
 
-template <int NH, bool TAPS>
+template <int NH, bool TAPS, bool SCORED>
 __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAVES_PER_EU))) void window_kernel(Geom G, WinArgs A)
 {
     constexpr int C = NH * 32, KS = NH, LPT = WinCfg<NH>::LPT, NV = WinCfg<NH>::NV, NT = NH * 64;
     static_assert(NT / LPT >= TOK, "one pass must cover the window");
     __shared__ v4i a1s[2 * KS * 64];                                     // LN1 codes as fragments [token block][k slab][lane]
     __shared__ __attribute__((aligned(16))) int csum[NH][HD];
+    __shared__ int red[NH];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, g = lane >> 5;
-    int branch, row0, canon_slot;
-    slot_info(G, blockIdx.x, branch, row0, canon_slot);
-    const int w = A.perm[canon_slot];
-    const int bimg = canon_slot / G.nW;
+    // SCORED: the workgroup is given a window and finds its own place in the selection (its rank
+    // under the total order of the scores); otherwise it is given a slot and looks the window up.
+    int branch = 0, row0 = 0, canon_slot = 0, w, bimg;
+    if (SCORED) {
+        bimg = blockIdx.x / G.nW;
+        w = blockIdx.x - bimg * G.nW;
+    } else {
+        slot_info(G, blockIdx.x, branch, row0, canon_slot);
+        w = A.perm[canon_slot];
+        bimg = canon_slot / G.nW;
+    }
     int* a1w = (int*)a1s;
     // dword index of (token slot s, channel c with c%4==0) in the fragment layout (k = channel, natural order)
     auto frag_dw = [&](int s, int c) { return ((((s >> 5) * KS + (c >> 5)) * 64 + ((c & 31) >> 4) * 32 + (s & 31)) << 2) + ((c & 15) >> 2); };
     for (int i = tid; i < 15 * (C / 4); i += NT) a1w[frag_dw(TOK + i / (C / 4), (i % (C / 4)) * 4)] = 0;
-    {
-        const int t = tid / LPT, sub = tid % LPT;
-        if (t < TOK) {
-            const int wr = w / G.nWc, wc = w - wr * G.nWc, tr = t / WS, tc = t - tr * WS;
-            int pr = wr * WS + tr + G.shift; if (pr >= G.Hp) pr -= G.Hp;
-            int pc = wc * WS + tc + G.shift; if (pc >= G.Wp) pc -= G.Wp;
-            const int pix = (pr < G.H && pc < G.W) ? (bimg * G.H + pr) * G.W + pc : -1;
-            const int canon = canon_slot * TOK + t;
-            if (sub == 0) { A.row_pix[row0 + t] = pix; A.row_canon[row0 + t] = canon; }
-            float4 v[NV];
+    const int t = tid / LPT, sub = tid % LPT;
+    int pix = -1;
+    float4 v[NV];
+    if (t < TOK) {                                                       // gather: the loads need the window only
+        const int wr = w / G.nWc, wc = w - wr * G.nWc, tr = t / WS, tc = t - tr * WS;
+        int pr = wr * WS + tr + G.shift; if (pr >= G.Hp) pr -= G.Hp;
+        int pc = wc * WS + tc + G.shift; if (pc >= G.Wp) pc -= G.Wp;
+        pix = (pr < G.H && pc < G.W) ? (bimg * G.H + pr) * G.W + pc : -1;
+        if (pix >= 0) {
+            const float* src = A.x + (size_t)pix * C;
+#pragma unroll
+            for (int k = 0; k < NV; ++k) v[k] = *(const float4*)(src + (k * LPT + sub) * 4);
+        }
+    }
+    if (SCORED) {
+        const double* sc = A.scores + (size_t)bimg * G.nW;
+        const double sw = sc[w];
+        const double nan = __longlong_as_double(0x7ff8000000000000LL);
+        int cnt = 0;
+        for (int base = 0; base < G.nW; base += 8 * NT) {                // eight loads in flight per thread
+            double sv[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) { const int u = base + tid + k * NT; sv[k] = u < G.nW ? sc[u] : nan; }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int u = base + tid + k * NT;
+                const bool ahead = A.reverse ? (sv[k] < sw) : (sv[k] > sw);
+                cnt += (ahead || (sv[k] == sw && u < w)) ? 1 : 0;
+            }
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
+        if (lane == 0) red[wave] = cnt;
+        __syncthreads();
+        int rank = 0;
+#pragma unroll
+        for (int k = 0; k < NH; ++k) rank += red[k];
+        if (tid == 0) A.perm_out[(size_t)bimg * G.nW + rank] = w;
+        if (rank >= G.k_hi + G.k_lo) {                                    // pruned (Sec. 3.4): forward the features
             if (pix >= 0) {
-                const float* src = A.x + (size_t)pix * C;
+                float* dst = A.y + (size_t)pix * C;
 #pragma unroll
-                for (int k = 0; k < NV; ++k) v[k] = *(const float4*)(src + (k * LPT + sub) * 4);
-                token_layernorm<LPT, NV>(v, C, A.eps, A.gamma[branch], A.beta[branch], sub);
-            } else {
-#pragma unroll
-                for (int k = 0; k < NV; ++k) v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int k = 0; k < NV; ++k) *(float4*)(dst + (k * LPT + sub) * 4) = v[k];
             }
-            const QDev q = A.q_in[branch];
+            return;                                                       // the whole workgroup
+        }
+        canon_slot = bimg * G.nW + rank;
+        if (rank < G.k_hi) { branch = 0; row0 = (bimg * G.k_hi + rank) * TOK; }
+        else { branch = 1; row0 = G.base_lo + (bimg * G.k_lo + rank - G.k_hi) * TOK; }
+    }
+    if (t < TOK) {
+        const int canon = canon_slot * TOK + t;
+        if (sub == 0) { A.row_pix[row0 + t] = pix; A.row_canon[row0 + t] = canon; }
+        if (pix >= 0) {
+            token_layernorm<LPT, NV>(v, C, A.eps, A.gamma[branch], A.beta[branch], sub);
+        } else {
 #pragma unroll
-            for (int k = 0; k < NV; ++k) {
-                const int ch = (k * LPT + sub) * 4;
-                int code = pack4(quant_code(v[k].x, q), quant_code(v[k].y, q), quant_code(v[k].z, q), quant_code(v[k].w, q));
-                a1w[frag_dw(t, ch)] = code;
-                if (TAPS && A.tap_a1) *(int*)(A.tap_a1 + (size_t)canon * C + ch) = code;
-            }
+            for (int k = 0; k < NV; ++k) v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        const QDev q = A.q_in[branch];
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const int ch = (k * LPT + sub) * 4;
+            int code = pack4(quant_code(v[k].x, q), quant_code(v[k].y, q), quant_code(v[k].z, q), quant_code(v[k].w, q));
+            a1w[frag_dw(t, ch)] = code;
+            if (TAPS && A.tap_a1) *(int*)(A.tap_a1 + (size_t)canon * C + ch) = code;
         }
     }
     __syncthreads();
@@ -943,11 +1004,18 @@ bool fused_supported(int C, int mlp_ratio) { return (C == 96 || C == 128 || C ==
 
 void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
 {
-    if (G.n_slots == 0) return;
-    dim3 grid(G.n_slots);
-#define WIN_CASE(NH)                                                                                     \
-    if (A.taps) hipLaunchKernelGGL((window_kernel<NH, true>), grid, dim3(NH * 64), 0, st, G, A);        \
-    else hipLaunchKernelGGL((window_kernel<NH, false>), grid, dim3(NH * 64), 0, st, G, A);              \
+    // with scores every window gets a workgroup (it may turn out pruned), otherwise every computed slot
+    const int n_wg = A.scores ? G.B * G.nW : G.n_slots;
+    if (n_wg == 0) return;
+    dim3 grid(n_wg);
+#define WIN_CASE(NH)                                                                                             \
+    if (A.scores) {                                                                                              \
+        if (A.taps) hipLaunchKernelGGL((window_kernel<NH, true, true>), grid, dim3(NH * 64), 0, st, G, A);      \
+        else hipLaunchKernelGGL((window_kernel<NH, false, true>), grid, dim3(NH * 64), 0, st, G, A);            \
+    } else {                                                                                                     \
+        if (A.taps) hipLaunchKernelGGL((window_kernel<NH, true, false>), grid, dim3(NH * 64), 0, st, G, A);     \
+        else hipLaunchKernelGGL((window_kernel<NH, false, false>), grid, dim3(NH * 64), 0, st, G, A);           \
+    }                                                                                                            \
     break
     switch (G.C / 32) {
         case 3: WIN_CASE(3);

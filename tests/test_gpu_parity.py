@@ -137,3 +137,30 @@ def test_activation_pruning_matches_oracle(shift, kh_frac, kl_frac, fused):
     oy, _ = O.block_forward(inp, x, o_perm, kh, k_low=kl)
     assert np.array_equal(y.cpu().numpy(), oy)
     assert torch.equal(y, y2)
+
+
+@pytest.mark.parametrize("C,heads", [(96, 3), (128, 4), (384, 12)])
+@pytest.mark.parametrize("shift,kh_frac,kl_frac", [(0, 0.5, -1), (3, 0.25, 0.5), (3, 0.0, 0.0)])
+def test_forward_from_scores_matches_oracle(C, heads, shift, kh_frac, kl_frac):
+    """The selection taken inside the first kernel from the stage's scores (fused path) or by the
+    select kernel (seven-kernel path, C = 384) gives the oracle's block output."""
+    import oracle_api as O
+    from paper_2507_19131_amd import binding as M
+    spec, inp, x, _ = _case(2, 26, 33, C, heads, shift, 0.5, 41, blobs=True)
+    nW = spec.nW
+    kh = int(kh_frac * nW)
+    kl = -1 if kl_frac < 0 else int(kl_frac * nW)
+    print("scored case", C, shift, kh, kl, flush=True)
+    dev = torch.device("cuda:0")
+    xt = torch.from_numpy(x).to(dev)
+    with gh.GpuBlock(inp) as gb:
+        scores = torch.empty((2, nW), dtype=torch.float64, device=dev)
+        M.mixaq_score_windows(gb.blk, xt, scores)
+        y = torch.full_like(xt, float("nan"))
+        perm_out = torch.full((2, nW), -1, dtype=torch.int32, device=dev)
+        M.mixaq_block_forward_scored(gb.blk, xt, scores, kh, kl, y, gb.ws, perm_out=perm_out)
+        torch.cuda.synchronize()
+    o_perm = O.select_windows(O.score_windows(inp, x), kh, k_low=None if kl < 0 else kl)
+    assert np.array_equal(perm_out.cpu().numpy(), o_perm)
+    oy, _ = O.block_forward(inp, x, o_perm, kh, k_low=None if kl < 0 else kl)
+    assert np.array_equal(y.cpu().numpy(), oy)
