@@ -27,32 +27,40 @@ def macs_per_window(C):
     return 588 * C * C + 4802 * C
 
 
+# VALU instructions per element of the pinned arithmetic (one lane-operation each): dequantize = cvt + fma,
+# quantize = fma + med3 + 3/4 pack, GELU = 18, LayerNorm = 8 (+ quantize), softmax element = 17 (+ quantize)
+ALU_DEQ, ALU_Q, ALU_GELU, ALU_LN, ALU_SOFTMAX = 2.0, 2.75, 18.0, 8.0, 17.0
+
+
 def kernel_model(name, C, F, heads, n_windows):
-    """Algorithmic work of one launch over n_windows windows: (bound, amount, unit-scale).
-    HBM kernels: bytes; MFMA kernels: int8 ops (2 per MAC)."""
+    """Algorithmic work of one launch over n_windows windows as (bound, amount): HBM kernels in bytes,
+    MFMA kernels in int8 operations (2 per MAC), ALU kernels in fp32 vector lane-operations.
+    The fused kernels are given BOTH their MFMA and their ALU work; the ALU side is the one that binds."""
     T = 49
+    mfma = None
     if name == "score":
-        return "hbm", n_windows * (4 * T * C + 8)
+        return "hbm", n_windows * (4 * T * C + 8), mfma
     if name == "select":
-        return "hbm", n_windows * (8 + 4)
-    if name == "gather_ln1_quant":
-        return "hbm", n_windows * (4 * T * C + T * C)
-    if name == "ln2_quant":
-        return "hbm", n_windows * (4 * T * C + T * C)
+        return "hbm", n_windows * (8 + 4), mfma
+    if name in ("gather_ln1_quant", "ln2_quant"):
+        return "hbm", n_windows * (4 * T * C + T * C), mfma
     if name == "qkv_gemm":
-        return "mfma", n_windows * 2 * T * C * 3 * C
+        return "mfma", n_windows * 2 * T * C * 3 * C, mfma
     if name == "window_attention":
-        return "mfma", n_windows * 2 * 2 * T * T * C
+        return "mfma", n_windows * 2 * 2 * T * T * C, mfma
     if name == "proj_gemm_residual":
-        return "mfma", n_windows * 2 * T * C * C
-    if name == "fc1_gemm_gelu":
-        return "mfma", n_windows * 2 * T * C * F
-    if name == "fc2_gemm_residual_scatter":
-        return "mfma", n_windows * 2 * T * C * F
+        return "mfma", n_windows * 2 * T * C * C, mfma
+    if name in ("fc1_gemm_gelu", "fc2_gemm_residual_scatter"):
+        return "mfma", n_windows * 2 * T * C * F, mfma
     if name == "window_ln1_qkv_attention":
-        return "mfma", n_windows * 2 * (T * C * 3 * C + 2 * T * T * C)
+        mfma = n_windows * 2 * (T * C * 3 * C + 2 * T * T * C)
+        alu = T * C * (ALU_LN + ALU_Q) + T * 3 * C * (ALU_DEQ + ALU_Q) + heads * T * T * (ALU_SOFTMAX + ALU_Q) + \
+            T * C * (ALU_DEQ + 1 + ALU_Q)
+        return "alu", n_windows * alu, mfma
     if name == "token_proj_ln2_ffn_scatter":
-        return "mfma", n_windows * 2 * (T * C * C + 2 * T * C * F)
+        mfma = n_windows * 2 * (T * C * C + 2 * T * C * F)
+        alu = T * C * (ALU_DEQ + 1) + T * C * (ALU_LN + ALU_Q) + T * F * (ALU_DEQ + ALU_GELU + ALU_Q) + T * C * (ALU_DEQ + 1)
+        return "alu", n_windows * alu, mfma
     raise KeyError(name)
 
 
@@ -160,18 +168,25 @@ def main():
         if not launches[n]:
             continue
         avg_ms = acc[n] / launches[n]
-        bound, amount = kernel_model(n, C, F, spec.heads, n_win)
+        bound, amount, mfma_ops = kernel_model(n, C, F, spec.heads, n_win)
         if bound == "hbm":
             ach, peak, unit = amount / (avg_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
-        else:
+        elif bound == "mfma":
             ach, peak, unit = amount / (avg_ms * 1e-3) / 1e12, PEAK_INT8_TOPS, "TOP/s"
+        else:
+            ach, peak, unit = amount / (avg_ms * 1e-3) / 1e12, PEAK_VALU_TLOPS, "Tlane-op/s"
         kernels[n] = dict(avg_ms=round(avg_ms, 5), launches_per_step=launches[n] // args.steps, bound=bound,
                           achieved=round(ach, 3), peak=peak, unit=unit, frac=round(ach / peak, 5))
+        if mfma_ops is not None:        # the same launch against the int8 MFMA peak
+            t = mfma_ops / (avg_ms * 1e-3) / 1e12
+            kernels[n].update(int8_tops=round(t, 3), frac_int8_mfma_peak=round(t / PEAK_INT8_TOPS, 5))
     per_step = {n: kernels[n]["avg_ms"] * kernels[n]["launches_per_step"] for n in kernels}
     dom = max(per_step, key=per_step.get)
     kd = kernels[dom]
     roofline = dict(kernel=dom, bound=kd["bound"], achieved=kd["achieved"], peak=kd["peak"], unit=kd["unit"],
                     frac=kd["frac"], traffic=read_traffic(dom), avg_ms=kd["avg_ms"])
+    if "frac_int8_mfma_peak" in kd:
+        roofline.update(int8_tops=kd["int8_tops"], frac_int8_mfma_peak=kd["frac_int8_mfma_peak"])
 
     windows_per_step = n_win * len(blocks)
     ops_per_step = 2 * macs_per_window(C) * windows_per_step

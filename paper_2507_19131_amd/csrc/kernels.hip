@@ -728,7 +728,7 @@ template <int C> struct TokPrm {
 };
 
 template <int NH, bool TAPS>
-__global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(TOK_WAVES_PER_EU, TOK_WAVES_PER_EU))) void token_kernel(Geom G, TokArgs A)
+__global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(NH <= 4 ? TOK_WAVES_PER_EU : 3, NH <= 4 ? TOK_WAVES_PER_EU : 3))) void token_kernel(Geom G, TokArgs A)
 {
     constexpr int C = NH * 32, KS = NH, HB = 4 * NH, F = 4 * C, NT = NH * 64;
     using PR = TokPrm<C>;
@@ -740,16 +740,15 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(TOK_WAV
     __shared__ __attribute__((aligned(16))) float prm[PR::WORDS];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, g = lane >> 5;
     const int row = blockIdx.x * 32 + j;
-    const int branch = row >= G.base_lo ? 1 : 0;
+    const int branch = (int)blockIdx.x * 32 >= G.base_lo ? 1 : 0;      // a tile never straddles the regions: scalar
     const bool valid = branch ? (row - G.base_lo < G.rows_lo) : (row < G.rows_hi);
     const int nb = wave;
     // ---- loads that depend on nothing: parameter block, attention codes, first weight fragments
-    float4 pv[PVT];
-    {
-        const float4* psrc = (const float4*)A.params[branch];
-#pragma unroll
-        for (int k = 0; k < PVT; ++k) { const int idx = tid + k * NT; if (idx < PV) pv[k] = psrc[idx]; }
-    }
+    static_assert(PVT <= 3, "the parameter block is staged with at most three loads per thread");
+    const float4* psrc = (const float4*)A.params[branch];
+    const float4 pv0 = psrc[tid];                                     // PV >= NT always; out-of-range threads re-read the last vector
+    const float4 pv1 = psrc[min(tid + NT, PV - 1)];
+    const float4 pv2 = psrc[min(tid + 2 * NT, PV - 1)];
     const int pix = valid ? A.row_pix[row] : -1;
     const size_t canon = (TAPS && valid) ? (size_t)A.row_canon[row] : 0;
     const bool tap_ok = TAPS && valid;
@@ -761,8 +760,9 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(TOK_WAV
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) { aof[ks] = *(const v4i*)(ap + ks * 32); wpf[ks] = wp[ks * 64]; w1f[ks] = w1[ks * 64]; }
     }
-#pragma unroll
-    for (int k = 0; k < PVT; ++k) { const int idx = tid + k * NT; if (idx < PV) ((float4*)prm)[idx] = pv[k]; }
+    ((float4*)prm)[tid] = pv0;
+    if (PVT > 1 && tid + NT < PV) ((float4*)prm)[tid + NT] = pv1;
+    if (PVT > 2 && tid + 2 * NT < PV) ((float4*)prm)[tid + 2 * NT] = pv2;
     float4 sc[4];
 #pragma unroll
     for (int qd = 0; qd < 4; ++qd)
