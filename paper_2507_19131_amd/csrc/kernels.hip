@@ -739,8 +739,9 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(NH <= 4
     __shared__ double part[2][NH][32];
     __shared__ __attribute__((aligned(16))) float prm[PR::WORDS];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, g = lane >> 5;
-    const int row = blockIdx.x * 32 + j;
-    const int branch = (int)blockIdx.x * 32 >= G.base_lo ? 1 : 0;      // a tile never straddles the regions: scalar
+    const int tile = blockIdx.x;
+    const int row = tile * 32 + j;
+    const int branch = tile * 32 >= G.base_lo ? 1 : 0;                 // a tile never straddles the regions: scalar
     const bool valid = branch ? (row - G.base_lo < G.rows_lo) : (row < G.rows_hi);
     const int nb = wave;
     // ---- loads that depend on nothing: parameter block, attention codes, first weight fragments
