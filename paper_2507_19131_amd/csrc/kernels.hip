@@ -12,24 +12,33 @@
 namespace mixaq {
 
 // ------------------------------------------------------------------ helpers
+// sum over a group of W consecutive lanes (the group does not straddle a wave); every lane of the
+// group gets the same bits: a butterfly for powers of two, a fixed-order gather otherwise
+// (first = the group's first lane).
 template <int W>
-__device__ __forceinline__ double group_sum(double v)
+__device__ __forceinline__ double group_sum(double v, int first = 0)
 {
+    if ((W & (W - 1)) == 0) {
 #pragma unroll
-    for (int o = W / 2; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+        for (int o = W / 2; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+        return v;
+    }
+    double tot = __shfl(v, first, 64);
+#pragma unroll
+    for (int k = 1; k < W; ++k) tot += __shfl(v, first + k, 64);
+    return tot;
 }
 
 // LayerNorm of one token spread over LPT lanes (NV float4 per lane; channel of
 // element e of vector k on lane i: (k*LPT + i)*4 + e).  Mean and variance in
 // binary64, rounded once.
 template <int LPT, int NV>
-__device__ __forceinline__ void token_ln_stats(const float4 (&v)[NV], int C, float eps, float& mean, float& rstd)
+__device__ __forceinline__ void token_ln_stats(const float4 (&v)[NV], int C, float eps, float& mean, float& rstd, int first = 0)
 {
     double s = 0.0;
 #pragma unroll
     for (int k = 0; k < NV; ++k) s += ((double)v[k].x + (double)v[k].y) + ((double)v[k].z + (double)v[k].w);
-    s = group_sum<LPT>(s);
+    s = group_sum<LPT>(s, first);
     mean = (float)(s / (double)C);
     double q = 0.0;
 #pragma unroll
@@ -38,7 +47,7 @@ __device__ __forceinline__ void token_ln_stats(const float4 (&v)[NV], int C, flo
         double c = (double)v[k].z - (double)mean, d = (double)v[k].w - (double)mean;
         q += (a * a + b * b) + (c * c + d * d);
     }
-    q = group_sum<LPT>(q);
+    q = group_sum<LPT>(q, first);
     const float var = (float)(q / (double)C);
     rstd = 1.0f / sqrtf(var + eps);
 }
@@ -60,10 +69,10 @@ __device__ __forceinline__ void token_ln_apply(float4 (&v)[NV], float mean, floa
 
 template <int LPT, int NV>
 __device__ __forceinline__ void token_layernorm(float4 (&v)[NV], int C, float eps, const float* __restrict__ gamma,
-                                                const float* __restrict__ beta, int sub)
+                                                const float* __restrict__ beta, int sub, int first = 0)
 {
     float mean, rstd;
-    token_ln_stats<LPT, NV>(v, C, eps, mean, rstd);
+    token_ln_stats<LPT, NV>(v, C, eps, mean, rstd, first);
     token_ln_apply<LPT, NV>(v, mean, rstd, gamma, beta, sub);
 }
 
@@ -511,15 +520,19 @@ __global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
 #endif
 template <int NH>
 struct WinCfg {
-    static constexpr int LPT = NH == 3 ? 2 : (NH == 8 ? 8 : 4);     // lanes per token in the LN phase (49 tokens fit one pass)
-    static constexpr int NV = NH * 32 / (4 * LPT);
+    // lanes per token in the LN phase: NH (3, 4, 6 or 8), so that the 49 tokens fit one pass with about
+    // three quarters of the lanes busy; a wave holds 64/LPT whole groups
+    static constexpr int LPT = NH;
+    static constexpr int GPW = 64 / LPT;                             // groups (tokens) per wave
+    static constexpr int NV = NH * 32 / (4 * LPT);                   // float4 per lane = 8
 };
 
 template <int NH, bool TAPS, bool SCORED>
 __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAVES_PER_EU))) void window_kernel(Geom G, WinArgs A)
 {
     constexpr int C = NH * 32, KS = NH, LPT = WinCfg<NH>::LPT, NV = WinCfg<NH>::NV, NT = NH * 64;
-    static_assert(NT / LPT >= TOK, "one pass must cover the window");
+    constexpr int GPW = WinCfg<NH>::GPW;
+    static_assert(NH * GPW >= TOK, "one pass must cover the window");
     __shared__ v4i a1s[2 * KS * 64];                                     // LN1 codes as fragments [token block][k slab][lane]
     __shared__ __attribute__((aligned(16))) int csum[NH][HD];
     __shared__ int red[NH];
@@ -539,7 +552,8 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
     // dword index of (token slot s, channel c with c%4==0) in the fragment layout (k = channel, natural order)
     auto frag_dw = [&](int s, int c) { return ((((s >> 5) * KS + (c >> 5)) * 64 + ((c & 31) >> 4) * 32 + (s & 31)) << 2) + ((c & 15) >> 2); };
     for (int i = tid; i < 15 * (C / 4); i += NT) a1w[frag_dw(TOK + i / (C / 4), (i % (C / 4)) * 4)] = 0;
-    const int t = tid / LPT, sub = tid % LPT;
+    const int grp = lane / LPT, sub = lane - grp * LPT, first = lane - sub;
+    const int t = grp < GPW ? wave * GPW + grp : TOK;                    // lanes beyond the last whole group idle
     int pix = -1;
     float4 v[NV];
     if (t < TOK) {                                                       // gather: the loads need the window only
@@ -593,7 +607,7 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
         const int canon = canon_slot * TOK + t;
         if (sub == 0) { A.row_pix[row0 + t] = pix; A.row_canon[row0 + t] = canon; }
         if (pix >= 0) {
-            token_layernorm<LPT, NV>(v, C, A.eps, A.gamma[branch], A.beta[branch], sub);
+            token_layernorm<LPT, NV>(v, C, A.eps, A.gamma[branch], A.beta[branch], sub, first);
         } else {
 #pragma unroll
             for (int k = 0; k < NV; ++k) v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
