@@ -50,19 +50,36 @@ static inline float orc_exp2_pinned(float y)
     return ldexpf(p, (int)n);
 }
 
-/* GELU(x) = x*Phi(x) = max(x,0) - a*Phi(-a), a = |x|.  The even remainder
- * a*Phi(-a) is a degree-14 polynomial in t = 2a/5.5 - 1 on a in [0,5.5] and is
- * held at its (1e-7) end value beyond. */
+/* GELU in the erf form, GELU(x) = x*Phi(x) = max(x,0) - H(|x|) with the even
+ * remainder H(a) = a*Phi(-a) = (a/2)*erfc(a/sqrt 2).  H is pinned as a piecewise
+ * cubic: [0,6) is cut into 96 intervals of width 1/16; on interval i the cubic in
+ * d = 16a - i interpolates H at the four points a = (3i+j)/48, j = 0..3 (both
+ * ends and the thirds), its coefficients computed in binary64 and rounded to
+ * binary32; beyond a = 6 the argument is held at the end of the last interval
+ * (H(6) < 1e-8).  The table is filled when the library is loaded. */
+#define ORC_GELU_INTERVALS 96
+static float orc_gelu_tab[ORC_GELU_INTERVALS][4];
+static inline double orc_gelu_remainder(double a) { return (0.5 * a) * erfc(a * 0.70710678118654752440); }
+__attribute__((constructor)) static void orc_gelu_fill_table(void)
+{
+    for (int i = 0; i < ORC_GELU_INTERVALS; ++i) {
+        double y[4];
+        for (int j = 0; j < 4; ++j) y[j] = orc_gelu_remainder((double)(3 * i + j) / 48.0);
+        orc_gelu_tab[i][0] = (float)y[0];
+        orc_gelu_tab[i][1] = (float)((-11.0 * y[0] + 18.0 * y[1] - 9.0 * y[2] + 2.0 * y[3]) * 0.5);
+        orc_gelu_tab[i][2] = (float)((18.0 * y[0] - 45.0 * y[1] + 36.0 * y[2] - 9.0 * y[3]) * 0.5);
+        orc_gelu_tab[i][3] = (float)((-9.0 * y[0] + 27.0 * y[1] - 27.0 * y[2] + 9.0 * y[3]) * 0.5);
+    }
+}
 static inline float orc_gelu_pinned(float x)
 {
-    static const float c[15] = {
-        0x1.0c8760p-7f, -0x1.f0423cp-5f, 0x1.8794f2p-3f, -0x1.3c122ap-2f, 0x1.711f2ap-3f,
-        0x1.0a7892p-2f, -0x1.46f9bap-1f, 0x1.d7ab76p-2f, 0x1.88e9f6p-3f, -0x1.18547cp-1f,
-        0x1.7cae60p-3f, 0x1.e1f934p-3f, -0x1.3d2fc0p-3f, -0x1.42e9b8p-5f, 0x1.280820p-5f };
-    float a = fminf(fabsf(x), 5.5f);
-    float t = fmaf(a, 0x1.745d18p-2f, -1.0f);
-    float h = c[14];
-    for (int k = 13; k >= 0; --k) h = fmaf(h, t, c[k]);
+    float u = fminf(fabsf(x) * 16.0f, 0x1.7ffffep+6f);  /* largest binary32 below 96 */
+    float fl = floorf(u);
+    float d = u - fl;                                   /* exact */
+    const float *c = orc_gelu_tab[(int)fl];
+    float h = fmaf(c[3], d, c[2]);
+    h = fmaf(h, d, c[1]);
+    h = fmaf(h, d, c[0]);
     return fmaxf(x, 0.0f) - h;
 }
 

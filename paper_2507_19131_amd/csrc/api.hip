@@ -26,6 +26,27 @@ int fail(int code, const char* fmt, ...)
     va_end(ap);
     return code;
 }
+// Cubic coefficients of the GELU remainder H(a) = (a/2) erfc(a / sqrt 2): on interval i the cubic in the
+// local coordinate d in [0,1) passes through H at the interval's ends and thirds.  Binary64 throughout,
+// one rounding to binary32 per coefficient.
+void gelu_table(float* tab)
+{
+    static const double lagrange[3][4] = {{-11.0, 18.0, -9.0, 2.0}, {18.0, -45.0, 36.0, -9.0}, {-9.0, 27.0, -27.0, 9.0}};
+    const double nodes_per_unit = 3.0 * (double)(1 << GELU_LOG2K);
+    for (int i = 0; i < GELU_K; ++i) {
+        double y[4];
+        for (int j = 0; j < 4; ++j) {
+            const double a = (double)(3 * i + j) / nodes_per_unit;
+            y[j] = (0.5 * a) * std::erfc(a * 0.70710678118654752440);
+        }
+        tab[4 * i] = (float)y[0];
+        for (int k = 0; k < 3; ++k) {
+            double acc = lagrange[k][0] * y[0];
+            for (int j = 1; j < 4; ++j) acc += lagrange[k][j] * y[j];
+            tab[4 * i + 1 + k] = (float)(acc * 0.5);
+        }
+    }
+}
 }  // namespace mixaq
 
 namespace {
@@ -119,6 +140,7 @@ struct mixaq_block {
     QDev q_in[2], q_qkv[2][3], q_p[2], q_ao[2], q_fc1in[2], q_fc2in[2];
     float m2[2], m_o[2];
     float* tok_params[2] = {nullptr, nullptr};   // parameter blocks of the fused token kernel
+    const float4* gelu_tab = nullptr;            // cubic coefficients of the pinned GELU
     size_t ws_bytes = 0;
     int rows_max = 0;
     bool fused = false;        // window + token kernels instead of the seven-kernel path
@@ -304,7 +326,8 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, co
         wa.tap_o = tp.acc_o; wa.tap_code = tp.a_proj_in;
         ta.tap_acc_proj = tp.acc_proj; ta.tap_h = tp.h; ta.tap_a2 = tp.a_fc1_in; ta.tap_acc_fc1 = tp.acc_fc1;
         ta.tap_g = tp.a_fc2_in; ta.tap_acc_fc2 = tp.acc_fc2; ta.tap_y = tp.y_win;
-        wa.poly = ta.poly = pinned_coefficients();
+        wa.poly = pinned_coefficients();
+        ta.gelu_tab = blk->gelu_tab;
         wa.taps = ta.taps = taps != nullptr;
         mark(9);
         for (int r = 0; r < reps; ++r) launch_window(G, wa, st);
@@ -327,7 +350,7 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, co
         a.A = act; a.Wp = L.Wp; a.K = L.K; a.N = L.N;
         for (int br = 0; br < 2; ++br) { a.m[br] = L.m[br]; a.bias[br] = L.bias[br]; a.negcorr[br] = L.negcorr[br]; }
         a.row_pix = ws.row_pix; a.row_canon = ws.row_canon;
-        a.poly = pinned_coefficients();
+        a.gelu_tab = blk->gelu_tab;
     };
     GemmArgs ga;
     fill(ga, blk->qkv, ws.a1);
@@ -482,6 +505,13 @@ int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* 
                     }
         }
         if ((rc = upload(b->owned, tab, &b->bias2))) return bail(rc);
+    }
+    {
+        std::vector<float> tab((size_t)GELU_K * 4);
+        gelu_table(tab.data());
+        float* dev = nullptr;
+        if ((rc = upload(b->owned, tab, &dev))) return bail(rc);
+        b->gelu_tab = (const float4*)dev;
     }
     b->fused = fused_supported(C, desc->mlp_ratio);
     if (b->fused) {     // parameter blocks of the token kernel: device-to-device gathers of what was just uploaded

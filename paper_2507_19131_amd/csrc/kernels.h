@@ -6,16 +6,15 @@ namespace mixaq {
 
 enum { EPI_QKV = 0, EPI_PROJ = 1, EPI_FC1 = 2, EPI_FC2 = 3 };
 
-// the pinned polynomial coefficients (host side fills kernel arguments with them)
+// the pinned coefficients of 2^r (host side fills kernel arguments with them)
 inline PolyCoef pinned_coefficients()
 {
-    PolyCoef P = {{0x1.000002p+0f, 0x1.62e430p-1f, 0x1.ebf906p-3f, 0x1.c6aeccp-5f, 0x1.3d107cp-7f, 0x1.5f48c8p-10f},
-                  {0x1.0c8760p-7f, -0x1.f0423cp-5f, 0x1.8794f2p-3f, -0x1.3c122ap-2f, 0x1.711f2ap-3f, 0x1.0a7892p-2f,
-                   -0x1.46f9bap-1f, 0x1.d7ab76p-2f, 0x1.88e9f6p-3f, -0x1.18547cp-1f, 0x1.7cae60p-3f, 0x1.e1f934p-3f,
-                   -0x1.3d2fc0p-3f, -0x1.42e9b8p-5f, 0x1.280820p-5f},
-                  0x1.745d18p-2f};
+    PolyCoef P = {{0x1.000002p+0f, 0x1.62e430p-1f, 0x1.ebf906p-3f, 0x1.c6aeccp-5f, 0x1.3d107cp-7f, 0x1.5f48c8p-10f}};
     return P;
 }
+
+// Host side: the GELU_K x 4 coefficient table of gelu_pinned (api.hip uploads it once per block).
+void gelu_table(float* tab);
 
 struct LnArgs {
     const int* perm;                 // [B,nW] (gather only)
@@ -48,7 +47,7 @@ struct GemmArgs {
     int32_t* tap_acc;
     int8_t* tap_code;
     float* tap_f;
-    PolyCoef poly;
+    const float4* gelu_tab;          // [GELU_K] cubic coefficients (FC1 epilogue)
 };
 
 struct AttnArgs {
@@ -109,7 +108,7 @@ struct TokArgs {                     // fused token kernel (proj + LN2 + FFN + s
     float eps;
     QDev q_fc1in[2], q_fc2in[2];
     int32_t* tap_acc_proj; float* tap_h; int8_t* tap_a2; int32_t* tap_acc_fc1; int8_t* tap_g; int32_t* tap_acc_fc2; float* tap_y;
-    PolyCoef poly;
+    const float4* gelu_tab;          // [GELU_K] cubic coefficients
     bool taps;
 };
 

@@ -231,7 +231,7 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(Geom G, LnArgs A)
 // A wave computes 64 rows x 32 channels at a time.
 template <int EPI>
 __device__ __forceinline__ void epilogue(const GemmArgs& A, const Geom& G, int branch, int row, int nb, int g,
-                                         const v16i& acc, int pix, int canon)
+                                         const v16i& acc, int pix, int canon, const float4* gelu_lds)
 {
     const int N = A.N;
 #pragma unroll
@@ -244,7 +244,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& A, const Geom& G, int b
         float f2 = fmaf((float)a2, m.z, bs.z), f3 = fmaf((float)a3, m.w, bs.w);
         if (A.tap_acc && canon >= 0) *(int4*)(A.tap_acc + (size_t)canon * N + n0) = make_int4(a0, a1, a2, a3);
         if (EPI == EPI_QKV || EPI == EPI_FC1) {
-            if (EPI == EPI_FC1) { f0 = gelu_pinned(f0, A.poly); f1 = gelu_pinned(f1, A.poly); f2 = gelu_pinned(f2, A.poly); f3 = gelu_pinned(f3, A.poly); }
+            if (EPI == EPI_FC1) { f0 = gelu_pinned(f0, gelu_lds); f1 = gelu_pinned(f1, gelu_lds); f2 = gelu_pinned(f2, gelu_lds); f3 = gelu_pinned(f3, gelu_lds); }
             const QDev& q = A.q[branch][EPI == EPI_QKV ? n0 / G.C : 0];
             int code = pack4(quant_code(f0, q), quant_code(f1, q), quant_code(f2, q), quant_code(f3, q));
             *(int*)(A.out8 + (size_t)row * N + n0) = code;
@@ -268,6 +268,12 @@ template <int KS, int EPI>      // KS = K/32 when the activation fragments fit i
 __global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 31, g = lane >> 5;
+    __shared__ float4 gtab[EPI == EPI_FC1 ? GELU_K : 1];
+    if (EPI == EPI_FC1) {
+        gelu_stage_table(gtab, A.gelu_tab, threadIdx.x, 256);
+        __syncthreads();
+    }
+    const float4* gelu_lds = gtab;
     const int tile = blockIdx.x * 4 + wave;
     if (tile * ROW_TILE >= G.rows_total) return;
     const int row0 = tile * ROW_TILE;
@@ -312,8 +318,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
                 c1 = mfma32(w, x1, c1);
             }
         }
-        epilogue<EPI>(A, G, branch, row0 + j, nb, g, c0, pix[0], canon[0]);
-        epilogue<EPI>(A, G, branch, row0 + 32 + j, nb, g, c1, pix[1], canon[1]);
+        epilogue<EPI>(A, G, branch, row0 + j, nb, g, c0, pix[0], canon[0], gelu_lds);
+        epilogue<EPI>(A, G, branch, row0 + 32 + j, nb, g, c1, pix[1], canon[1], gelu_lds);
     }
 }
 
@@ -752,6 +758,7 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(NH <= 4
     __shared__ v4i gs[HB * 64];
     __shared__ double part[2][NH][32];
     __shared__ __attribute__((aligned(16))) float prm[PR::WORDS];
+    __shared__ float4 gtab[GELU_K];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, g = lane >> 5;
     const int tile = blockIdx.x;
     const int row = tile * 32 + j;
@@ -775,6 +782,8 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(NH <= 4
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) { aof[ks] = *(const v4i*)(ap + ks * 32); wpf[ks] = wp[ks * 64]; w1f[ks] = w1[ks * 64]; }
     }
+    gelu_stage_table(gtab, A.gelu_tab, tid, NT);
+    const float4* gelu_lds = gtab;
     ((float4*)prm)[tid] = pv0;
     if (PVT > 1 && tid + NT < PV) ((float4*)prm)[tid + NT] = pv1;
     if (PVT > 2 && tid + 2 * NT < PV) ((float4*)prm)[tid + 2 * NT] = pv2;
@@ -880,10 +889,10 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(NH <= 4
             for (int qd = 0; qd < 4; ++qd) {
                 const int n0 = hb * 32 + qd * 8 + g * 4;
                 const float4 m = *(const float4*)(prm + PR::F1_M + n0), bs = *(const float4*)(prm + PR::F1_B + n0);
-                wd[qd] = pack4(quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 0], m.x, bs.x), A.poly), qg),
-                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 1], m.y, bs.y), A.poly), qg),
-                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 2], m.z, bs.z), A.poly), qg),
-                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 3], m.w, bs.w), A.poly), qg));
+                wd[qd] = pack4(quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 0], m.x, bs.x), gelu_lds), qg),
+                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 1], m.y, bs.y), gelu_lds), qg),
+                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 2], m.z, bs.z), gelu_lds), qg),
+                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 3], m.w, bs.w), gelu_lds), qg));
                 if (tap_ok) {
                     if (A.tap_acc_fc1) *(int4*)(A.tap_acc_fc1 + canon * F + n0) = make_int4(acc[qd * 4], acc[qd * 4 + 1], acc[qd * 4 + 2], acc[qd * 4 + 3]);
                     if (A.tap_g) *(int*)(A.tap_g + canon * F + n0) = wd[qd];

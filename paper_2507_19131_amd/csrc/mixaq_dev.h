@@ -47,12 +47,10 @@ __device__ __forceinline__ int pack4(int c0, int c1, int c2, int c3)
     return lo | hi;
 }
 
-// Coefficients of the two pinned polynomials.  They travel as kernel arguments so that they sit
+// Coefficients of the pinned exponential.  They travel as kernel arguments so that they sit
 // in scalar registers and every Horner step is one v_fma with a scalar addend.
 struct PolyCoef {
     float e[6];       // 2^r on [-1/2, 1/2], degree 5, e[0] = constant term
-    float g[15];      // a*Phi(-a) in t = 2a/5.5 - 1, degree 14, g[0] = constant term
-    float gscale;     // 2/5.5
 };
 
 // 2^y for y <= 0 (clamped at -100): split, degree-5 polynomial, exact scaling.
@@ -70,15 +68,24 @@ __device__ __forceinline__ float exp2_pinned(float y, const PolyCoef& P)
     return ldexpf(p, (int)n);
 }
 
-// GELU(x) = max(x,0) - a*Phi(-a), a = |x|; the remainder is a degree-14 polynomial
-// in t = 2a/5.5 - 1 for a <= 5.5 and constant beyond.
-__device__ __forceinline__ float gelu_pinned(float x, const PolyCoef& P)
+// GELU(x) = max(x,0) - H(|x|), H(a) = a*Phi(-a) as a piecewise cubic: interval i of width
+// 2^-GELU_LOG2K on [0,6) holds the cubic in d = fract(a * 2^GELU_LOG2K); beyond the last
+// interval the argument is held at its end.  The coefficient table (one float4 per interval)
+// lives in LDS; replicating it per lane group to spread the banks was measured and is no faster.
+constexpr int GELU_LOG2K = 4;
+constexpr int GELU_K = 6 << GELU_LOG2K;                       // intervals on [0,6)
+__device__ __forceinline__ void gelu_stage_table(float4* lds, const float4* tab, int tid, int nthreads)
 {
-    float a = fminf(fabsf(x), 5.5f);
-    float t = fmaf(a, P.gscale, -1.0f);
-    float h = P.g[14];
-#pragma unroll
-    for (int k = 13; k >= 0; --k) h = fmaf(h, t, P.g[k]);
+    for (int e = tid; e < GELU_K; e += nthreads) lds[e] = tab[e];
+}
+__device__ __forceinline__ float gelu_pinned(float x, const float4* lds)
+{
+    const float u = fminf(fabsf(x) * (float)(1 << GELU_LOG2K), (float)GELU_K * 0x1.fffffep-1f);
+    const float d = __builtin_amdgcn_fractf(u);
+    const float4 c = lds[(int)u];
+    float h = fmaf(c.w, d, c.z);
+    h = fmaf(h, d, c.y);
+    h = fmaf(h, d, c.x);
     return fmaxf(x, 0.0f) - h;
 }
 

@@ -41,7 +41,10 @@ def test_gelu_pinned_against_erf_form():
     x = np.linspace(-12.0, 12.0, 2_400_001).astype(np.float32)
     got = _arr_fn(L.orc_gelu_array, x).astype(np.float64)
     ref = x.astype(np.float64) * ndtr(x.astype(np.float64))
-    assert np.max(np.abs(got - ref)) <= 1e-6
+    assert np.max(np.abs(got - ref)) <= 5e-7          # half an ulp of the result at |x| >= 4 is 2.4e-7
+    near = np.abs(x) <= 1.0
+    assert np.max(np.abs(got[near] - ref[near])) <= 1.2e-7
+    assert L.orc_gelu(0.0) == 0.0
     big = np.array([20.0, 1e3, 1e6, -20.0, -1e3, -1e6], dtype=np.float32)
     g = _arr_fn(L.orc_gelu_array, big)
     assert np.all(np.abs(g[:3] - big[:3]) <= 1e-6) and np.all(np.abs(g[3:]) <= 1e-6)
