@@ -629,32 +629,48 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
     }
     __syncthreads();
     const int head = wave;
-    v4i bf[2][KS];
+    // Operand handling.  Up to eight heads the LN1 fragments of both token blocks and the weight
+    // fragments of one output block sit in registers; beyond that the B operand is read from LDS
+    // inside the chain and the weight fragments stream through a short ring.
+    constexpr bool HOIST = NH <= 8;
+    constexpr int RING = 6;
+    v4i bf[2][HOIST ? KS : 1];
+    if (HOIST) {
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
+        for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) bf[tb][ks] = a1s[(tb * KS + ks) * 64 + lane];
+            for (int ks = 0; ks < KS; ++ks) bf[tb][ks] = a1s[(tb * KS + ks) * 64 + lane];
+    }
+    // streaming form: acc[tb] += (weights as A operand ? W * act^T : act * W^T) over the whole K
+    auto chain = [&](const v4i* wp, v16i* acc, bool weights_first) {
+        v4i ring[RING];
+#pragma unroll
+        for (int d = 0; d < RING; ++d) ring[d] = wp[d * 64];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const v4i wv = ring[ks % RING];
+            if (ks + RING < KS) ring[ks % RING] = wp[(ks + RING) * 64];
+            const v4i x0 = a1s[ks * 64 + lane], x1 = a1s[(KS + ks) * 64 + lane];
+            acc[0] = weights_first ? mfma32(wv, x0, acc[0]) : mfma32(x0, wv, acc[0]);
+            acc[1] = weights_first ? mfma32(wv, x1, acc[1]) : mfma32(x1, wv, acc[1]);
+        }
+    };
     const size_t canon_row0 = (size_t)canon_slot * TOK;
     v4i qk[2][2];                                                        // [q|k][token block]
 #pragma unroll
     for (int which = 0; which < 2; ++which) {
         const int nb = which * NH + head;
-        const v4i* wp = A.Wqkv + (size_t)nb * KS * 64 + lane;
-        v4i wf[KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) wf[ks] = wp[ks * 64];
         const QDev qq = A.q_qkv[branch][which];
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-            v16i acc;
+        const v4i* wp = A.Wqkv + (size_t)nb * KS * 64 + lane;
+        auto start = [&](v16i& acc) {                                     // accumulators start at -zp * colsum
             const int* nc = A.negcorr[branch] + nb * 32 + g * 4;
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 int4 t4 = *(const int4*)(nc + qd * 8);
                 acc[qd * 4 + 0] = t4.x; acc[qd * 4 + 1] = t4.y; acc[qd * 4 + 2] = t4.z; acc[qd * 4 + 3] = t4.w;
             }
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) acc = mfma32(wf[ks], bf[tb][ks], acc);
+        };
+        auto finish = [&](int tb, const v16i& acc) {                      // dequantize, requantize, keep as operand
             int wd[4];
             const int tok = tb * 32 + j;
 #pragma unroll
@@ -670,26 +686,37 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
                 }
             }
             qk[which][tb] = (v4i){wd[0], wd[1], wd[2], wd[3]};
+        };
+        if (HOIST) {
+            v4i wf[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) wf[ks] = wp[ks * 64];
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                v16i acc;
+                start(acc);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) acc = mfma32(wf[ks], bf[tb][ks], acc);
+                finish(tb, acc);
+            }
+        } else {
+            v16i acc[2];
+            start(acc[0]);
+            acc[1] = acc[0];
+            chain(wp, acc, true);
+            finish(0, acc[0]);
+            finish(1, acc[1]);
         }
     }
     v4i vt[2];
     {
         const int nb = 2 * NH + head, n = nb * 32 + j;                   // this lane's output channel (dim j of the head)
         const v4i* wp = A.Wqkv + (size_t)nb * KS * 64 + lane;
-        v4i wf[KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) wf[ks] = wp[ks * 64];
         const float m = A.m[branch][n], bs = A.bias[branch][n];
         const int nc = A.negcorr[branch][n];
         const QDev qv = A.q_qkv[branch][2];
         int cs = 0;
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-            v16i acc;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = nc;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) acc = mfma32(bf[tb][ks], wf[ks], acc);          // rows = tokens, columns = dims
+        auto finish = [&](int tb, const v16i& acc) {
             int wd[4];
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
@@ -710,6 +737,28 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
                 cs = __builtin_amdgcn_sdot4(wd[qd], 0x01010101, cs, false);
             }
             vt[tb] = (v4i){wd[0], wd[1], wd[2], wd[3]};
+        };
+        if (HOIST) {
+            v4i wf[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) wf[ks] = wp[ks * 64];
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                v16i acc;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[r] = nc;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) acc = mfma32(bf[tb][ks], wf[ks], acc);      // rows = tokens, columns = dims
+                finish(tb, acc);
+            }
+        } else {
+            v16i acc[2];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[0][r] = nc;
+            acc[1] = acc[0];
+            chain(wp, acc, false);
+            finish(0, acc[0]);
+            finish(1, acc[1]);
         }
         cs += __shfl_xor(cs, 32, 64);
         if (g == 0) csum[wave][j] = cs;
@@ -930,6 +979,215 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(NH <= 4
     }
 }
 
+// ------------------------------------------------------------------ fused token kernel, streaming form
+// For the wider stages (C >= 192), where re-reading all 12 C^2 weight bytes per 32 rows would bind on
+// L2 bandwidth.  One workgroup per tile of 64 gathered rows (two 32-row blocks share every weight
+// fragment), one wave per 32-channel block.  The K = C operands (attention codes, then LN2 codes) are
+// staged once in LDS as fragments; weight fragments stream from L2 through a ring of RING loads in
+// flight; the FFN is cut into four chunks of NH hidden blocks: FC1 + GELU + quantize of a chunk goes to
+// one of two LDS buffers, then FC2 accumulates that chunk, so the hidden activations never exist as
+// a whole.  Epilogue constants are read from the per-branch parameter block in global memory.
+#ifndef TOKEN_RING
+#define TOKEN_RING(NH) ((NH) == 8 ? 8 : (NH) == 12 ? 12 : 6)   // weight fragments in flight per wave
+#endif
+template <int NH, bool TAPS>
+__global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A)
+{
+    constexpr int C = NH * 32, KS = NH, HB = 4 * NH, F = 4 * C, NT = NH * 64, RING = TOKEN_RING(NH);
+    static_assert(NH % RING == 0, "a chain is a whole number of ring turns");
+    using PR = TokPrm<C>;
+    __shared__ v4i actf[2 * KS * 64];                                 // [row block][k slab][lane]
+    __shared__ v4i gs[2][NH * 2 * 64];                                // [buffer][hidden block of the chunk][row block][lane]
+    __shared__ double part[2][NH][64];
+    __shared__ float4 gtab[GELU_K];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, g = lane >> 5;
+    const int tile = blockIdx.x, row_base = tile * 64;
+    const int branch = row_base >= G.base_lo ? 1 : 0;                 // a tile never straddles the regions: scalar
+    const int nb = wave;
+    const float* prm = A.params[branch];
+    const int* prmi = (const int*)prm;
+    int pix[2];
+    bool valid[2];
+    size_t canon[2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        const int row = row_base + rb * 32 + j;
+        valid[rb] = branch ? (row - G.base_lo < G.rows_lo) : (row < G.rows_hi);
+        pix[rb] = valid[rb] ? A.row_pix[row] : -1;
+        canon[rb] = (TAPS && valid[rb]) ? (size_t)A.row_canon[row] : 0;
+    }
+    // stage the attention codes of the tile: piece p = (row r, 16-byte chunk q) -> fragment (r/32, q/2), lane (r%32, q%2)
+    for (int p = tid; p < 64 * (C / 16); p += NT) {
+        const int r = p / (C / 16), q = p - r * (C / 16);
+        actf[((r >> 5) * KS + (q >> 1)) * 64 + (q & 1) * 32 + (r & 31)] = *(const v4i*)(A.ao + (size_t)(row_base + r) * C + q * 16);
+    }
+    gelu_stage_table(gtab, A.gelu_tab, tid, NT);
+    float4 sc[2][4];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd)
+            sc[rb][qd] = pix[rb] >= 0 ? *(const float4*)(A.x + (size_t)pix[rb] * C + nb * 32 + qd * 8 + g * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+    // acc[rb] += W(fragments wp[0], wp[64], ...) * operand fragments b[(rb * stride_rb + i) * 64 + lane]
+    auto start = [&](v16i* acc, int off) {                             // accumulators start at -zp * colsum
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            const int4 t4 = *(const int4*)(prmi + off + qd * 8 + g * 4);
+            acc[0][qd * 4 + 0] = t4.x; acc[0][qd * 4 + 1] = t4.y; acc[0][qd * 4 + 2] = t4.z; acc[0][qd * 4 + 3] = t4.w;
+        }
+        acc[1] = acc[0];
+    };
+    v4i ring[RING];
+    auto request = [&](const v4i* wp) {
+#pragma unroll
+        for (int d = 0; d < RING; ++d) ring[d] = wp[d * 64];
+    };
+    // acc[rb] += W * operand^T over n fragments: weights from the ring (refilled n fragments ahead
+    // from wp), operand fragment i of row block rb at b[(rb * rb_stride + i * i_stride) * 64 + lane]
+    auto chain = [&](const v4i* wp, const v4i* b, int rb_stride, int i_stride, int n, v16i* acc) {
+#pragma unroll 1
+        for (int i0 = 0; i0 < n; i0 += RING) {
+#pragma unroll
+            for (int d = 0; d < RING; ++d) {
+                const int i = i0 + d;
+                const v4i wv = ring[d];
+                if (i + RING < n) ring[d] = wp[(i + RING) * 64];
+                acc[0] = mfma32(wv, b[(i * i_stride) * 64 + lane], acc[0]);
+                acc[1] = mfma32(wv, b[(rb_stride + i * i_stride) * 64 + lane], acc[1]);
+            }
+        }
+    };
+    __syncthreads();                                                  // staged codes and table visible
+    float h[2][16];
+    {   // output projection + first residual
+        const v4i* wp = A.Wproj + (size_t)nb * KS * 64 + lane;
+        request(wp);
+        v16i acc[2];
+        start(acc, PR::P_NC + nb * 32);
+        chain(wp, actf, KS, 1, KS, acc);
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                const int n0 = nb * 32 + qd * 8 + g * 4;
+                const float4 m = *(const float4*)(prm + PR::P_M + n0), bs = *(const float4*)(prm + PR::P_B + n0);
+                h[rb][qd * 4 + 0] = fmaf((float)acc[rb][qd * 4 + 0], m.x, bs.x) + sc[rb][qd].x;
+                h[rb][qd * 4 + 1] = fmaf((float)acc[rb][qd * 4 + 1], m.y, bs.y) + sc[rb][qd].y;
+                h[rb][qd * 4 + 2] = fmaf((float)acc[rb][qd * 4 + 2], m.z, bs.z) + sc[rb][qd].z;
+                h[rb][qd * 4 + 3] = fmaf((float)acc[rb][qd * 4 + 3], m.w, bs.w) + sc[rb][qd].w;
+                if (TAPS && valid[rb]) {
+                    if (A.tap_acc_proj) *(int4*)(A.tap_acc_proj + canon[rb] * C + n0) = make_int4(acc[rb][qd * 4], acc[rb][qd * 4 + 1], acc[rb][qd * 4 + 2], acc[rb][qd * 4 + 3]);
+                    if (A.tap_h) *(float4*)(A.tap_h + canon[rb] * C + n0) = make_float4(h[rb][qd * 4], h[rb][qd * 4 + 1], h[rb][qd * 4 + 2], h[rb][qd * 4 + 3]);
+                }
+            }
+    }
+    request(A.W1 + (size_t)wave * KS * 64 + lane);                    // first FC1 chain, in flight during LN2
+    {   // LN2: binary64 partial sums per (wave, token) through LDS, then normalise and quantize
+        float mean[2], rstd[2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            double s = 0.0;
+#pragma unroll
+            for (int r = 0; r < 16; r += 4) s += ((double)h[rb][r] + (double)h[rb][r + 1]) + ((double)h[rb][r + 2] + (double)h[rb][r + 3]);
+            s += __shfl_xor(s, 32, 64);
+            if (g == 0) part[0][wave][rb * 32 + j] = s;
+        }
+        __syncthreads();                                              // also: every wave is done reading the attention codes
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            double tot = 0.0;
+#pragma unroll
+            for (int w2 = 0; w2 < NH; ++w2) tot += part[0][w2][rb * 32 + j];
+            mean[rb] = (float)(tot / (double)C);
+            double q = 0.0;
+#pragma unroll
+            for (int r = 0; r < 16; r += 4) {
+                double a = (double)h[rb][r] - (double)mean[rb], b = (double)h[rb][r + 1] - (double)mean[rb];
+                double c = (double)h[rb][r + 2] - (double)mean[rb], d = (double)h[rb][r + 3] - (double)mean[rb];
+                q += (a * a + b * b) + (c * c + d * d);
+            }
+            q += __shfl_xor(q, 32, 64);
+            if (g == 0) part[1][wave][rb * 32 + j] = q;
+        }
+        __syncthreads();
+        const QDev qa = A.q_fc1in[branch];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            double tot = 0.0;
+#pragma unroll
+            for (int w2 = 0; w2 < NH; ++w2) tot += part[1][w2][rb * 32 + j];
+            const float var = (float)(tot / (double)C);
+            rstd[rb] = 1.0f / sqrtf(var + A.eps);
+            int wd[4];
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                const int n0 = nb * 32 + qd * 8 + g * 4;
+                const float4 gm = *(const float4*)(prm + PR::LN_G + n0), bt = *(const float4*)(prm + PR::LN_B + n0);
+                wd[qd] = pack4(quant_code(fmaf((h[rb][qd * 4 + 0] - mean[rb]) * rstd[rb], gm.x, bt.x), qa),
+                               quant_code(fmaf((h[rb][qd * 4 + 1] - mean[rb]) * rstd[rb], gm.y, bt.y), qa),
+                               quant_code(fmaf((h[rb][qd * 4 + 2] - mean[rb]) * rstd[rb], gm.z, bt.z), qa),
+                               quant_code(fmaf((h[rb][qd * 4 + 3] - mean[rb]) * rstd[rb], gm.w, bt.w), qa));
+                if (TAPS && valid[rb] && A.tap_a2) *(int*)(A.tap_a2 + canon[rb] * C + n0) = wd[qd];
+            }
+            actf[(rb * KS + nb) * 64 + lane] = (v4i){wd[0], wd[1], wd[2], wd[3]};   // k slab nb, byte r = channel 32nb + mfma_row(r,g)
+        }
+    }
+    __syncthreads();
+    v16i acc2[2];
+    start(acc2, PR::F2_NC + nb * 32);
+    const QDev qg = A.q_fc2in[branch];
+#pragma unroll 1
+    for (int ch = 0; ch < 4; ++ch) {
+        const int hb = ch * NH + wave;
+        {   // FC1 + GELU + quantize of hidden block hb
+            const v4i* wp = A.W1 + (size_t)hb * KS * 64 + lane;
+            v16i acc[2];
+            start(acc, PR::F1_NC + hb * 32);
+            chain(wp, actf, KS, 1, KS, acc);
+            request(A.W2 + ((size_t)nb * HB + ch * NH) * 64 + lane); // FC2 fragments of this chunk, in flight during the epilogue
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                int wd[4];
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    const int n0 = hb * 32 + qd * 8 + g * 4;
+                    const float4 m = *(const float4*)(prm + PR::F1_M + n0), bs = *(const float4*)(prm + PR::F1_B + n0);
+                    wd[qd] = pack4(quant_code(gelu_pinned(fmaf((float)acc[rb][qd * 4 + 0], m.x, bs.x), gtab), qg),
+                                   quant_code(gelu_pinned(fmaf((float)acc[rb][qd * 4 + 1], m.y, bs.y), gtab), qg),
+                                   quant_code(gelu_pinned(fmaf((float)acc[rb][qd * 4 + 2], m.z, bs.z), gtab), qg),
+                                   quant_code(gelu_pinned(fmaf((float)acc[rb][qd * 4 + 3], m.w, bs.w), gtab), qg));
+                    if (TAPS && valid[rb]) {
+                        if (A.tap_acc_fc1) *(int4*)(A.tap_acc_fc1 + canon[rb] * F + n0) = make_int4(acc[rb][qd * 4], acc[rb][qd * 4 + 1], acc[rb][qd * 4 + 2], acc[rb][qd * 4 + 3]);
+                        if (A.tap_g) *(int*)(A.tap_g + canon[rb] * F + n0) = wd[qd];
+                    }
+                }
+                gs[ch & 1][(wave * 2 + rb) * 64 + lane] = (v4i){wd[0], wd[1], wd[2], wd[3]};
+            }
+        }
+        __syncthreads();                                              // chunk ch of the hidden codes complete
+        {   // FC2 over the chunk's NH hidden blocks
+            const v4i* wp = A.W2 + ((size_t)nb * HB + ch * NH) * 64 + lane;
+            const v4i* gb = gs[ch & 1];
+            chain(wp, gb, 1, 2, NH, acc2);
+            if (ch < 3) request(A.W1 + (size_t)(hb + NH) * KS * 64 + lane);
+        }
+    }
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {   // second residual + scatter
+            const int n0 = nb * 32 + qd * 8 + g * 4;
+            const float4 m = *(const float4*)(prm + PR::F2_M + n0), bs = *(const float4*)(prm + PR::F2_B + n0);
+            float4 o4 = make_float4(fmaf((float)acc2[rb][qd * 4 + 0], m.x, bs.x) + h[rb][qd * 4 + 0], fmaf((float)acc2[rb][qd * 4 + 1], m.y, bs.y) + h[rb][qd * 4 + 1],
+                                    fmaf((float)acc2[rb][qd * 4 + 2], m.z, bs.z) + h[rb][qd * 4 + 2], fmaf((float)acc2[rb][qd * 4 + 3], m.w, bs.w) + h[rb][qd * 4 + 3]);
+            if (pix[rb] >= 0) *(float4*)(A.y + (size_t)pix[rb] * C + n0) = o4;
+            if (TAPS && valid[rb]) {
+                if (A.tap_acc_fc2) *(int4*)(A.tap_acc_fc2 + canon[rb] * C + n0) = make_int4(acc2[rb][qd * 4], acc2[rb][qd * 4 + 1], acc2[rb][qd * 4 + 2], acc2[rb][qd * 4 + 3]);
+                if (A.tap_y) *(float4*)(A.tap_y + canon[rb] * C + n0) = o4;
+            }
+        }
+}
+
 // ------------------------------------------------------------------ launchers
 template <int LPT, int NV>
 static void launch_score_t(const Geom& G, const float* x, int mode, float eps, const float* gm, const float* bt,
@@ -1024,7 +1282,7 @@ void launch_gemm(const Geom& G, const GemmArgs& A, int epi, hipStream_t st)
     }
 }
 
-bool fused_supported(int C, int mlp_ratio) { return (C == 96 || C == 128 || C == 192 || C == 256) && mlp_ratio == 4; }
+bool fused_supported(int C, int mlp_ratio) { return (C == 96 || C == 128 || C == 192 || C == 256 || C == 384) && mlp_ratio == 4; }
 
 void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
 {
@@ -1045,26 +1303,43 @@ void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
         case 3: WIN_CASE(3);
         case 4: WIN_CASE(4);
         case 6: WIN_CASE(6);
-        default: WIN_CASE(8);
+        case 8: WIN_CASE(8);
+        default: WIN_CASE(12);
     }
 #undef WIN_CASE
 }
 
+#ifndef TOKEN_STREAM_FROM
+#define TOKEN_STREAM_FROM 12         // NH from which the streaming 64-row form is used (measured: the 32-row form wins below)
+#endif
 void launch_token(const Geom& G, const TokArgs& A, hipStream_t st)
 {
     if (G.rows_total == 0) return;
-    dim3 grid(G.rows_total / 32);
-#define TOK_CASE(NH)                                                                                     \
-    if (A.taps) hipLaunchKernelGGL((token_kernel<NH, true>), grid, dim3(NH * 64), 0, st, G, A);         \
-    else hipLaunchKernelGGL((token_kernel<NH, false>), grid, dim3(NH * 64), 0, st, G, A);               \
+    const int NHr = G.C / 32;
+#define TOK_CASE(NH)                                                                                              \
+    if (A.taps) hipLaunchKernelGGL((token_kernel<NH, true>), dim3(G.rows_total / 32), dim3(NH * 64), 0, st, G, A); \
+    else hipLaunchKernelGGL((token_kernel<NH, false>), dim3(G.rows_total / 32), dim3(NH * 64), 0, st, G, A);      \
     break
-    switch (G.C / 32) {
-        case 3: TOK_CASE(3);
-        case 4: TOK_CASE(4);
-        case 6: TOK_CASE(6);
-        default: TOK_CASE(8);
+#define STREAM_CASE(NH)                                                                                                  \
+    if (A.taps) hipLaunchKernelGGL((token_stream_kernel<NH, true>), dim3(G.rows_total / 64), dim3(NH * 64), 0, st, G, A); \
+    else hipLaunchKernelGGL((token_stream_kernel<NH, false>), dim3(G.rows_total / 64), dim3(NH * 64), 0, st, G, A);      \
+    break
+    if (NHr >= TOKEN_STREAM_FROM) {
+        switch (NHr) {
+            case 6: STREAM_CASE(6);
+            case 8: STREAM_CASE(8);
+            default: STREAM_CASE(12);
+        }
+    } else {
+        switch (NHr) {
+            case 3: TOK_CASE(3);
+            case 4: TOK_CASE(4);
+            case 6: TOK_CASE(6);
+            default: TOK_CASE(8);
+        }
     }
 #undef TOK_CASE
+#undef STREAM_CASE
 }
 
 void launch_attn(const Geom& G, const AttnArgs& A, hipStream_t st)
