@@ -114,17 +114,9 @@ def main():
     bufs = [torch.empty_like(x), torch.empty_like(x)]
 
     def step():
-        # score once for the stage; the first block takes the selection from the scores inside its first
-        # kernel and hands the list to the stage's other blocks
-        M.mixaq_score_windows(blocks[0], x, scores)
-        cur = x
-        for i, blk in enumerate(blocks):
-            if i == 0:
-                M.mixaq_block_forward_scored(blk, cur, scores, k_high, -1, bufs[i % 2], ws, perm_out=perm)
-            else:
-                M.mixaq_block_forward(blk, cur, perm, k_high, bufs[i % 2], ws)
-            cur = bufs[i % 2]
-        return cur
+        # one C call for the stage: score once; the first block takes the selection from the scores inside
+        # its first kernel and leaves the list for the stage's other blocks
+        return M.mixaq_stage_forward(blocks, x, [k_high], None, bufs[0], bufs[1], scores, perm, ws)
 
     for _ in range(args.warmup):
         step()

@@ -165,6 +165,24 @@ int mixaq_block_forward_pruned(const mixaq_block *blk, const float *x, const int
 int mixaq_block_forward_scored(const mixaq_block *blk, const float *x, const double *scores, int32_t k_high,
                                int32_t k_low, float *y, int32_t *perm_out, void *workspace, size_t workspace_bytes,
                                void *stream);
+
+/* One stage (Sec. 3.2: the importance scores are computed a single time, on the stage's input,
+ * and shared by all of its blocks; Sec. 3.3: blocks 2p and 2p+1 form pair p and share one
+ * compression ratio).  blocks: HOST array of n_blocks handles created on the same map shape
+ * [B,H,W,C] (normally alternating shift 0 / 3).  k_high, k_low: HOST arrays with one entry per
+ * pair (ceil(n_blocks/2)); k_low may be NULL (no pruning).  Runs: scores on x; block 0 takes its
+ * selection from the scores and leaves the full list of windows sorted by importance in perm;
+ * every later block reads that list with its own pair's counts.  Pruned windows of a block carry
+ * their features through that block unchanged (Sec. 3.4).  x is not modified; the result lands
+ * in y; tmp is a second map-sized device buffer the blocks alternate with (x, y, tmp must not
+ * overlap).  scores (device double [B,nW]) and perm (device int32 [B,nW]) are caller-owned scratch
+ * that hold the stage's scores and selection list afterwards.  The workspace must satisfy
+ * mixaq_block_workspace_bytes of the stage's blocks (equal shapes give equal sizes).  All work is
+ * enqueued on `stream`; nothing is allocated.  MIXAQ_E_SHAPE if the blocks disagree on the shape
+ * or a count is out of range, MIXAQ_E_NULL for missing pointers. */
+int mixaq_stage_forward(mixaq_block *const *blocks, int32_t n_blocks, const float *x, const int32_t *k_high,
+                        const int32_t *k_low, float *y, float *tmp, double *scores, int32_t *perm, void *workspace,
+                        size_t workspace_bytes, void *stream);
 /* Same as mixaq_block_forward, and also fills the given taps. */
 int mixaq_block_forward_taps(const mixaq_block *blk, const float *x, const int32_t *perm, int32_t k_high,
                              float *y, void *workspace, size_t workspace_bytes, void *stream,

@@ -81,6 +81,8 @@ def load():
                                                   C.c_void_p, C.c_size_t, C.c_void_p, C.c_int32, C.POINTER(C.c_float)]
         L.mixaq_block_forward_scored.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                                  C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.mixaq_stage_forward.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.mixaq_block_set_fused.argtypes = [C.c_void_p, C.c_int32]
         L.mixaq_kernel_name.restype = C.c_char_p
         L.mixaq_kernel_name.argtypes = [C.c_int32]
@@ -235,6 +237,17 @@ def mixaq_kernel_name(i):
 def mixaq_block_forward_scored(blk, x, scores, k_high, k_low, y, workspace, perm_out=None, stream=None):
     _check(load().mixaq_block_forward_scored(blk, _ptr(x), _ptr(scores), k_high, k_low, _ptr(y), _ptr(perm_out), _ptr(workspace),
                                              workspace.numel() * workspace.element_size(), _stream(stream)))
+    return y
+
+
+def mixaq_stage_forward(blocks, x, k_high, k_low, y, tmp, scores, perm, workspace, stream=None):
+    """blocks: list of handles; k_high / k_low: one int per block pair (k_low None = no pruning)."""
+    n = len(blocks)
+    handles = (C.c_void_p * n)(*[b.value if isinstance(b, C.c_void_p) else b for b in blocks])
+    kh = (C.c_int32 * len(k_high))(*[int(v) for v in k_high])
+    kl = (C.c_int32 * len(k_low))(*[int(v) for v in k_low]) if k_low is not None else None
+    _check(load().mixaq_stage_forward(handles, n, _ptr(x), kh, kl, _ptr(y), _ptr(tmp), _ptr(scores), _ptr(perm), _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream(stream)))
     return y
 
 

@@ -305,7 +305,7 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, co
         for (int r = 0; r < reps; ++r) launch_select(scores, d.B, blk->nW, 0, perm_out ? perm_out : ws.perm, st);
         perm = perm_out ? perm_out : ws.perm;
     }
-    if (!in_kernel_select) launch_bypass(G, perm, x, y, st);       // pruned windows (if any) are forwarded
+    if (!blk->fused) launch_bypass(G, perm, x, y, st);             // pruned windows (if any) are forwarded; the fused window kernel does it itself
     if (blk->fused) {
         WinArgs wa = {};
         wa.x = x; wa.perm = perm; wa.scores = in_kernel_select ? scores : nullptr; wa.reverse = 0; wa.perm_out = perm_out ? perm_out : ws.perm;
@@ -593,6 +593,38 @@ int mixaq_block_forward_scored(const mixaq_block* blk, const float* x, const dou
     if (!scores) return fail(MIXAQ_E_NULL, "scores is NULL");
     return forward_impl(blk, x, nullptr, scores, k_high, k_low, y, workspace, workspace_bytes, stream, nullptr, nullptr,
                         perm_out);
+}
+
+int mixaq_stage_forward(mixaq_block* const* blocks, int32_t n_blocks, const float* x, const int32_t* k_high,
+                        const int32_t* k_low, float* y, float* tmp, double* scores, int32_t* perm, void* workspace,
+                        size_t workspace_bytes, void* stream)
+{
+    if (!blocks || !x || !k_high || !y || !scores || !perm) return fail(MIXAQ_E_NULL, "a required pointer is NULL");
+    if (n_blocks < 1) return fail(MIXAQ_E_SHAPE, "n_blocks = %d", n_blocks);
+    if (n_blocks > 1 && !tmp) return fail(MIXAQ_E_NULL, "tmp is NULL (needed for more than one block)");
+    for (int i = 0; i < n_blocks; ++i) {
+        if (!blocks[i]) return fail(MIXAQ_E_NULL, "blocks[%d] is NULL", i);
+        const mixaq_block_desc &a = blocks[0]->d, &b = blocks[i]->d;
+        if (a.B != b.B || a.H != b.H || a.W != b.W || a.C != b.C)
+            return fail(MIXAQ_E_SHAPE, "blocks[%d] was created for another map shape", i);
+    }
+    const int nW = blocks[0]->nW;
+    for (int p = 0; p < (n_blocks + 1) / 2; ++p) {
+        const int kh = k_high[p], kl = k_low ? k_low[p] : nW - kh;
+        if (kh < 0 || kl < 0 || kh + kl > nW) return fail(MIXAQ_E_SHAPE, "pair %d: k_high %d, k_low %d of %d windows", p, kh, kl, nW);
+    }
+    int rc = mixaq_score_windows(blocks[0], x, scores, stream);
+    if (rc) return rc;
+    const float* cur = x;
+    for (int i = 0; i < n_blocks; ++i) {
+        float* dst = ((n_blocks - 1 - i) & 1) ? tmp : y;            // the last block writes y
+        const int kh = k_high[i / 2], kl = k_low ? k_low[i / 2] : nW - kh;
+        if (i == 0) rc = forward_impl(blocks[0], cur, nullptr, scores, kh, kl, dst, workspace, workspace_bytes, stream, nullptr, nullptr, perm);
+        else rc = forward_impl(blocks[i], cur, perm, nullptr, kh, kl, dst, workspace, workspace_bytes, stream, nullptr, nullptr, nullptr);
+        if (rc) return rc;
+        cur = dst;
+    }
+    return MIXAQ_OK;
 }
 
 int mixaq_block_forward_pruned(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, int32_t k_low,

@@ -549,10 +549,24 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
     if (SCORED) {
         bimg = blockIdx.x / G.nW;
         w = blockIdx.x - bimg * G.nW;
-    } else {
+    } else if ((int)blockIdx.x < G.n_slots) {
         slot_info(G, blockIdx.x, branch, row0, canon_slot);
         w = A.perm[canon_slot];
         bimg = canon_slot / G.nW;
+    } else {                              // workgroups past the computed slots: pruned windows (Sec. 3.4), features forwarded
+        const int kept = G.k_hi + G.k_lo, q = blockIdx.x - G.n_slots, b = q / (G.nW - kept);
+        const int wp = A.perm[b * G.nW + kept + (q - b * (G.nW - kept))];
+        const int wr = wp / G.nWc, wc = wp - wr * G.nWc;
+        for (int i = tid; i < TOK * (C / 4); i += NT) {
+            const int tt = i / (C / 4), k = i - tt * (C / 4), tr = tt / WS, tc = tt - tr * WS;
+            int pr = wr * WS + tr + G.shift; if (pr >= G.Hp) pr -= G.Hp;
+            int pc = wc * WS + tc + G.shift; if (pc >= G.Wp) pc -= G.Wp;
+            if (pr < G.H && pc < G.W) {
+                const size_t off = ((size_t)(b * G.H + pr) * G.W + pc) * C + k * 4;
+                *(float4*)(A.y + off) = *(const float4*)(A.x + off);
+            }
+        }
+        return;
     }
     int* a1w = (int*)a1s;
     // dword index of (token slot s, channel c with c%4==0) in the fragment layout (k = channel, natural order)
@@ -1286,8 +1300,9 @@ bool fused_supported(int C, int mlp_ratio) { return (C == 96 || C == 128 || C ==
 
 void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
 {
-    // with scores every window gets a workgroup (it may turn out pruned), otherwise every computed slot
-    const int n_wg = A.scores ? G.B * G.nW : G.n_slots;
+    // every window gets a workgroup: with scores it finds its own rank (and may turn out pruned), otherwise
+    // the computed slots come first and the pruned windows of the list after them
+    const int n_wg = G.B * G.nW;
     if (n_wg == 0) return;
     dim3 grid(n_wg);
 #define WIN_CASE(NH)                                                                                             \

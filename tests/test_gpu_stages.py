@@ -77,3 +77,41 @@ def test_config5_swin_b_stages(stage):
     st = wl["stages"][stage]
     print("config 5 stage", stage, flush=True)
     check(*run_stage(st["spec"], st["shifts"], wl["keep"][0], wl["seed"] + stage, wl["blobs"], wl["outliers"], wl.get("ranges")))
+
+
+@pytest.mark.parametrize("fused", [True, False])
+def test_stage_entry_point_with_a_ratio_per_pair_and_pruning(fused):
+    """mixaq_stage_forward (one C call for the stage: score once, select inside the first block, every
+    pair with its own counts, Sec. 3.2-3.4) against the oracle's chain of blocks."""
+    spec = synth.BlockSpec(2, 33, 40, 96, 3)
+    shifts = [0, 3, 0, 3, 0]                                      # two pairs and a single last block
+    k_high, k_low = [12, 5, 20], [10, 25, 0]                       # nW = 30: pair 0 prunes 8 windows, pair 2 prunes 10
+    x_np = synth.make_feature_map(spec, 77, blobs=True)
+    inputs = [synth.make_block_inputs(spec, 700 + i) for i in range(len(shifts))]
+    assert spec.nW == 30
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(x_np).to(dev)
+    blocks = [gh.GpuBlock(inp, shift, fused) for inp, shift in zip(inputs, shifts)]
+    try:
+        y, tmp = torch.empty_like(x), torch.empty_like(x)
+        scores = torch.empty((spec.B, spec.nW), dtype=torch.float64, device=dev)
+        perm = torch.empty((spec.B, spec.nW), dtype=torch.int32, device=dev)
+        M.mixaq_stage_forward([gb.blk for gb in blocks], x, k_high, k_low, y, tmp, scores, perm, blocks[0].ws)
+        torch.cuda.synchronize()
+        assert torch.equal(x.cpu(), torch.from_numpy(x_np))        # the input is left alone
+        y_gpu, perm_gpu, scores_gpu = y.cpu().numpy(), perm.cpu().numpy(), scores.cpu().numpy()
+        with pytest.raises(M.MixaqError) as e:
+            M.mixaq_stage_forward([gb.blk for gb in blocks], x, [12, 5, 31], None, y, tmp, scores, perm, blocks[0].ws)
+        assert e.value.code == -2
+    finally:
+        for gb in blocks:
+            gb.close()
+    sc_o = O.score_windows(inputs[0], x_np)
+    assert np.array_equal(scores_gpu, sc_o) or np.allclose(scores_gpu, sc_o, rtol=1e-12, atol=0)
+    cur = x_np
+    for i, (inp, shift) in enumerate(zip(inputs, shifts)):
+        perm_o = O.select_windows(sc_o, k_high[i // 2], k_low=k_low[i // 2])
+        assert np.array_equal(perm_gpu, perm_o)                   # the list is the full sort: the same for every pair
+        cur, _ = O.block_forward(inp, cur, perm_o, k_high[i // 2], shift, threads=16, k_low=k_low[i // 2])
+    check(y_gpu, cur, perm_gpu, perm_o)
+    assert np.array_equal(y_gpu, cur)
