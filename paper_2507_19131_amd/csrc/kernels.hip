@@ -89,18 +89,31 @@ __global__ __launch_bounds__(256) void score_kernel(Geom G, const float* __restr
     const int grp = threadIdx.x / LPT, sub = threadIdx.x % LPT;
     constexpr int TP = 256 / LPT;
     double acc = 0.0;
-    for (int t = grp; t < TOK; t += TP) {
-        int pr = wr * WS + t / WS, pc = wc * WS + t % WS;
-        if (pr < G.H && pc < G.W) {                   // uniform inside a token group
-            const float* px = x + ((size_t)(b * G.H + pr) * G.W + pc) * G.C;
-            float4 v[NV];
+    constexpr int PASSES = (TOK + TP - 1) / TP;
+    constexpr int PC = LPT <= 16 ? PASSES : 2;        // passes whose loads are issued together, before any arithmetic
+#pragma unroll 1
+    for (int p0 = 0; p0 < PASSES; p0 += PC) {
+        float4 v[PC][NV];
+        bool in[PC];
 #pragma unroll
-            for (int k = 0; k < NV; ++k) v[k] = *(const float4*)(px + (k * LPT + sub) * 4);
-            if (mode == 1) token_layernorm<LPT, NV>(v, G.C, eps, gamma, beta, sub);
+        for (int p = 0; p < PC; ++p) {
+            const int t = grp + (p0 + p) * TP, pr = wr * WS + t / WS, pc = wc * WS + t % WS;
+            in[p] = t < TOK && pr < G.H && pc < G.W;  // uniform inside a token group
+            if (in[p]) {
+                const float* px = x + ((size_t)(b * G.H + pr) * G.W + pc) * G.C;
 #pragma unroll
-            for (int k = 0; k < NV; ++k)
-                acc += ((double)v[k].x * (double)v[k].x + (double)v[k].y * (double)v[k].y) +
-                       ((double)v[k].z * (double)v[k].z + (double)v[k].w * (double)v[k].w);
+                for (int k = 0; k < NV; ++k) v[p][k] = *(const float4*)(px + (k * LPT + sub) * 4);
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < PC; ++p) {
+            if (in[p]) {
+                if (mode == 1) token_layernorm<LPT, NV>(v[p], G.C, eps, gamma, beta, sub);
+#pragma unroll
+                for (int k = 0; k < NV; ++k)
+                    acc += ((double)v[p][k].x * (double)v[p][k].x + (double)v[p][k].y * (double)v[p][k].y) +
+                           ((double)v[p][k].z * (double)v[p][k].z + (double)v[p][k].w * (double)v[p][k].w);
+            }
         }
     }
     acc = group_sum<64>(acc);
