@@ -30,6 +30,9 @@ SMALL = [
     (1, 30, 30, 96, 3, 3, 0.0, 15, {}),                                               # everything low
     (1, 30, 30, 96, 3, 3, 1.0, 16, {}),                                               # everything high
     (3, 15, 16, 96, 3, 0, 0.11, 17, dict(blobs=True)),                                # one high window per image
+    (1, 28, 35, 96, 3, 3, 0.5, 18, dict(bits=(6, 3))),                                # odd bit widths
+    (2, 21, 21, 128, 4, 3, 0.6, 19, dict(bits=(5, 2), wbits=4)),                      # 2-bit low branch, 4-bit weights
+    (1, 7, 7, 96, 3, 0, 1.0, 20, {}),                                                 # a single window
 ]
 
 
@@ -55,6 +58,21 @@ def test_config2_full_size(shift, fused):
     res = gh.compare_block(inp, x, k, fused=fused)
     print(res, flush=True)
     gh.assert_parity(res)
+
+
+def test_maximum_window_count():
+    """4096 windows per image is the most the selection handles (448x448 map, shifted); more is refused."""
+    from paper_2507_19131_amd import binding as M
+    spec, inp, x, k = _case(1, 448, 448, 96, 3, 3, 0.5, 23, blobs=True)
+    assert spec.nW == 4096
+    print("maximum window count", flush=True)
+    res = gh.compare_block(inp, x, k, taps=("a_proj_in", "a_fc2_in"))
+    print(res, flush=True)
+    gh.assert_parity(res)
+    sh, br = M.to_device(inp)
+    with pytest.raises(M.MixaqError) as e:
+        M.mixaq_block_create(M.make_desc(synth.BlockSpec(1, 455, 448, 96, 3)), sh, br)
+    assert e.value.code == -2
 
 
 def test_order_invariance_and_reverse_selection():
@@ -139,11 +157,11 @@ def test_activation_pruning_matches_oracle(shift, kh_frac, kl_frac, fused):
     assert torch.equal(y, y2)
 
 
-@pytest.mark.parametrize("C,heads", [(96, 3), (128, 4), (384, 12)])
+@pytest.mark.parametrize("C,heads", [(96, 3), (128, 4), (384, 12), (768, 24)])
 @pytest.mark.parametrize("shift,kh_frac,kl_frac", [(0, 0.5, -1), (3, 0.25, 0.5), (3, 0.0, 0.0)])
 def test_forward_from_scores_matches_oracle(C, heads, shift, kh_frac, kl_frac):
     """The selection taken inside the first kernel from the stage's scores (fused path) or by the
-    select kernel (seven-kernel path, C = 384) gives the oracle's block output."""
+    select kernel (seven-kernel path, C = 768) gives the oracle's block output."""
     import oracle_api as O
     from paper_2507_19131_amd import binding as M
     spec, inp, x, _ = _case(2, 26, 33, C, heads, shift, 0.5, 41, blobs=True)
