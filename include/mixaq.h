@@ -188,6 +188,54 @@ int mixaq_block_forward_taps(const mixaq_block *blk, const float *x, const int32
                              float *y, void *workspace, size_t workspace_bytes, void *stream,
                              const mixaq_taps *taps);
 
+/* ---- layers between stages ---------------------------------------------------------------- */
+
+/* Patch embedding and patch merging of the Swin backbone the blocks sit in.  The paper keeps them
+ * outside MixA-Q (appendix on equivalent activation bits: the constant term of the cost model, the
+ * layers whose computation the method cannot save); they are offered so that the stages of a
+ * backbone can run as one chain.  Each is ONE uniformly quantized linear layer with the block's
+ * arithmetic (codes in int8 containers, int32 sums, f = fma(f32(acc - z*colsum), a_in.scale*s_w[n],
+ * bias[n])):
+ *   kind 0, patch embedding: token (i,j) takes the patch x patch x C_in values of its patch in the
+ *     order (row in patch, column in patch, channel), zero outside the image; quantize; linear
+ *     with bias; LayerNorm over the N outputs (ln_gamma, ln_beta: [N]).
+ *   kind 1, patch merging: the 2x2 neighbours with (row, column) offsets (0,0), (1,0), (0,1), (1,1)
+ *     concatenated along the channels (K = 4*C_in), zero outside the map; LayerNorm over the K
+ *     values (ln_gamma, ln_beta: [K]); quantize; linear (bias may be NULL).
+ * x: device float [B,H,W,C_in]; y: device float [B,Ho,Wo,N], Ho = ceil(H/P), Wo = ceil(W/P), P =
+ * patch (kind 0) or 2 (kind 1).  w: device int8 [N][K] codes, s_w: device float [N].  N must be a
+ * multiple of 32, K a multiple of 4 (kind 1: C_in a multiple of 4). */
+typedef struct {
+    int32_t kind;                    /* 0 = patch embedding, 1 = patch merging                   */
+    int32_t B, H, W, C_in;           /* input image / map                                        */
+    int32_t patch;                   /* kind 0: patch side (4); ignored for kind 1               */
+    int32_t N;                       /* output channels                                          */
+    int32_t act_bits, weight_bits;   /* 2..8                                                     */
+    float   ln_eps;
+} mixaq_downsample_desc;
+typedef struct {
+    const int8_t *w;
+    const float  *s_w;
+    const float  *bias;              /* [N] or NULL                                              */
+    const float  *ln_gamma, *ln_beta;
+    mixaq_qparam  a_in;              /* quantizer of the linear layer's input                    */
+} mixaq_downsample_params;
+typedef struct mixaq_downsample mixaq_downsample;
+
+/* Output map size and inputs per token of a descriptor (host only). */
+int mixaq_downsample_out_shape(const mixaq_downsample_desc *desc, int32_t *Ho, int32_t *Wo, int32_t *K);
+/* Copies and pre-packs the parameters into library-owned device memory (synchronous copies).
+ * MIXAQ_E_SHAPE / MIXAQ_E_BITS / MIXAQ_E_NULL on a bad descriptor or parameters. */
+int mixaq_downsample_create(const mixaq_downsample_desc *desc, const mixaq_downsample_params *params,
+                            mixaq_downsample **out);
+int mixaq_downsample_destroy(mixaq_downsample *h);
+/* One kernel on `stream`; allocates nothing; x and y must not overlap. */
+int mixaq_downsample_forward(const mixaq_downsample *h, const float *x, float *y, void *stream);
+/* The same, also writing the input codes (device int8 [tokens][K]) and the zero-point corrected
+ * int32 sums (device int32 [tokens][N]) for parity checks; either may be NULL. */
+int mixaq_downsample_forward_taps(const mixaq_downsample *h, const float *x, float *y, void *stream,
+                                  int8_t *tap_codes, int32_t *tap_acc);
+
 /* ---- host-only helpers (no GPU work) ------------------------------------------------------- */
 
 /* Equivalent activation bits (appendix "Calculation of Equivalent Activation Bits"):

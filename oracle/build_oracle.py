@@ -8,7 +8,7 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "liboracle.so")
-SOURCES = ["mixaq_oracle.c", "uniform_block.c"]
+SOURCES = ["mixaq_oracle.c", "uniform_block.c", "downsample.c"]
 
 
 def build(force=True):

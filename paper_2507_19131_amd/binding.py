@@ -52,6 +52,15 @@ class Taps(C.Structure):
     _fields_ = [(n, C.c_void_p) for n, _ in TAP_FIELDS]
 
 
+class DownsampleDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("kind", "B", "H", "W", "C_in", "patch", "N", "act_bits", "weight_bits")] + \
+               [("ln_eps", C.c_float)]
+
+
+class DownsampleParams(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("w", "s_w", "bias", "ln_gamma", "ln_beta")] + [("a_in", QParam)]
+
+
 def lib_path():
     return _LIB_PATH
 
@@ -83,6 +92,11 @@ def load():
                                                  C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.mixaq_stage_forward.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.mixaq_downsample_out_shape.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.mixaq_downsample_create.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]
+        L.mixaq_downsample_destroy.argtypes = [C.c_void_p]
+        L.mixaq_downsample_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.mixaq_downsample_forward_taps.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.mixaq_block_set_fused.argtypes = [C.c_void_p, C.c_int32]
         L.mixaq_kernel_name.restype = C.c_char_p
         L.mixaq_kernel_name.argtypes = [C.c_int32]
@@ -258,6 +272,51 @@ def mixaq_block_forward_profile(blk, x, perm, k_high, y, workspace, repeats=1, s
     _check(load().mixaq_block_forward_profile(blk, _ptr(x), _ptr(perm), _ptr(scores), k_high, _ptr(y), _ptr(workspace),
                                               workspace.numel() * workspace.element_size(), _stream(stream), int(repeats), ms))
     return {mixaq_kernel_name(i): float(ms[i]) for i in range(NUM_KERNELS)}
+
+
+def make_downsample_desc(spec):
+    """spec: synth.DownSpec (or any object with the same fields)."""
+    return DownsampleDesc(spec.kind, spec.B, spec.H, spec.W, spec.C_in, spec.patch, spec.N, spec.act_bits, spec.weight_bits,
+                          spec.ln_eps)
+
+
+def mixaq_downsample_out_shape(desc):
+    ho, wo, k = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(load().mixaq_downsample_out_shape(C.byref(desc), C.byref(ho), C.byref(wo), C.byref(k)))
+    return ho.value, wo.value, k.value
+
+
+def mixaq_downsample_create(desc, params):
+    """params: object with CUDA tensors w, s_w, bias (or None), ln_gamma, ln_beta and a_in = (scale, zero_point)."""
+    pp = DownsampleParams(_ptr(params.w), _ptr(params.s_w), _ptr(params.bias), _ptr(params.ln_gamma), _ptr(params.ln_beta),
+                          QParam(params.a_in[0], params.a_in[1]))
+    out = C.c_void_p()
+    _check(load().mixaq_downsample_create(C.byref(desc), C.byref(pp), C.byref(out)))
+    return out
+
+
+def mixaq_downsample_destroy(h):
+    _check(load().mixaq_downsample_destroy(h))
+
+
+def mixaq_downsample_forward(h, x, y, stream=None):
+    _check(load().mixaq_downsample_forward(h, _ptr(x), _ptr(y), _stream(stream)))
+    return y
+
+
+def mixaq_downsample_forward_taps(h, x, y, tap_codes=None, tap_acc=None, stream=None):
+    _check(load().mixaq_downsample_forward_taps(h, _ptr(x), _ptr(y), _stream(stream), _ptr(tap_codes), _ptr(tap_acc)))
+    return y
+
+
+def downsample_to_device(inp, device="cuda:0"):
+    """Copies the numpy arrays of a synth.DownInputs to the device."""
+    bag = _Bag()
+    for n in ("w", "s_w", "bias", "ln_gamma", "ln_beta"):
+        v = getattr(inp, n)
+        setattr(bag, n, None if v is None else torch.from_numpy(np.ascontiguousarray(v)).to(device))
+    bag.a_in = inp.a_in
+    return bag
 
 
 # ---------------------------------------------------------------- memory helpers (no arithmetic)

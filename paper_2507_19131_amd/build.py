@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmixaq.so")
-SOURCES = ["api.hip", "kernels.hip", "cost_sampler.cpp"]
+SOURCES = ["api.hip", "kernels.hip", "downsample.hip", "cost_sampler.cpp"]
 # -ffp-contract=off: the pinned binary32 sequences must not be re-fused;
 # packed fp32 instructions are disabled for the device pass.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-ffp-contract=off", "-fPIC", "-shared",

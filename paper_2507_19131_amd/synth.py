@@ -205,6 +205,96 @@ def make_block_inputs(spec, seed, ranges=None, asymmetric=True):
     return BlockInputs(spec, shared, branches)
 
 
+@dataclass
+class DownSpec:
+    """Shape and precision of a layer between stages (the fields of the C descriptor):
+    kind 0 = patch embedding (patch x patch x C_in values per token), kind 1 = patch merging."""
+    kind: int
+    B: int
+    H: int
+    W: int
+    C_in: int
+    N: int
+    patch: int = 4
+    act_bits: int = 8
+    weight_bits: int = 8
+    ln_eps: float = 1e-5
+
+    @property
+    def P(self):
+        return self.patch if self.kind == 0 else 2
+
+    @property
+    def K(self):
+        return self.P * self.P * self.C_in
+
+    @property
+    def Ho(self):
+        return -(-self.H // self.P)
+
+    @property
+    def Wo(self):
+        return -(-self.W // self.P)
+
+
+@dataclass
+class DownInputs:
+    spec: DownSpec
+    w: np.ndarray            # [N,K] int8 codes
+    s_w: np.ndarray          # [N]
+    bias: Optional[np.ndarray]
+    ln_gamma: np.ndarray     # kind 0: [N]; kind 1: [K]
+    ln_beta: np.ndarray
+    a_in: tuple              # (scale, zero_point)
+
+
+def make_image(B, H, W, seed, channels=3):
+    """Smooth noise (N(0,1) box-filtered over 16 pixels, rescaled to unit spread) plus a few
+    object-like elliptical blobs of raised magnitude; stands in for a detection-scale photograph."""
+    rng = _rng(seed, 20)
+    n = rng.standard_normal((B, H + 15, W + 15, channels))
+    c = np.cumsum(np.cumsum(n, axis=1), axis=2)
+    c = np.pad(c, ((0, 0), (1, 0), (1, 0), (0, 0)))
+    box = c[:, 16:, 16:] - c[:, :-16, 16:] - c[:, 16:, :-16] + c[:, :-16, :-16]
+    img = (box[:, :H, :W] / 16.0).astype(np.float32)
+    rr, cc = np.meshgrid(np.arange(H), np.arange(W), indexing="ij")
+    for b in range(B):
+        for _ in range(12):
+            cy, cx = rng.uniform(0, H), rng.uniform(0, W)
+            ay, ax = rng.uniform(0.03, 0.10) * H + 4, rng.uniform(0.03, 0.10) * W + 4
+            m = ((rr - cy) / ay) ** 2 + ((cc - cx) / ax) ** 2 <= 1.0
+            img[b][m] = np.float32(2.0) * img[b][m] + rng.standard_normal(channels).astype(np.float32)
+    return np.ascontiguousarray(img)
+
+
+def make_downsample_inputs(spec, seed, in_range=(-4.0, 4.5)):
+    """Weights ~ N(0, 0.02^2) (patch embedding: N(0, 0.2^2), its inputs are few), LayerNorm parameters,
+    bias (patch embedding only) and the input quantizer of a layer between stages."""
+    rng = _rng(seed, 30)
+    std = 0.2 if spec.kind == 0 else 0.02
+    w, s_w = quantize_weights(rng.standard_normal((spec.N, spec.K)) * std, spec.weight_bits)
+    n_ln = spec.N if spec.kind == 0 else spec.K
+    g = np.clip(1.0 + 0.25 * rng.standard_normal(n_ln), 0.25, 2.0).astype(np.float32)
+    b = (0.1 * rng.standard_normal(n_ln)).astype(np.float32)
+    bias = (0.02 * rng.standard_normal(spec.N)).astype(np.float32) if spec.kind == 0 else None
+    return DownInputs(spec, w, s_w, bias, g, b, qparam_for_range(in_range[0], in_range[1], spec.act_bits))
+
+
+def backbone(name="cfg4"):
+    """The whole backbone of a workload as a chain: patch embedding, then every stage, with a patch
+    merging between stages.  Returns dict(image=(B,H,W), embed=DownSpec, stages=[...], merges=[DownSpec...])."""
+    wl = workload(name)
+    st = wl["stages"]
+    s0 = st[0]["spec"]
+    bits, wbits = s0.act_bits_high, s0.weight_bits
+    embed = DownSpec(0, s0.B, s0.H * 4, s0.W * 4, 3, s0.C, patch=4, act_bits=bits, weight_bits=wbits)
+    merges = [DownSpec(1, a["spec"].B, a["spec"].H, a["spec"].W, a["spec"].C, b["spec"].C, act_bits=bits, weight_bits=wbits)
+              for a, b in zip(st[:-1], st[1:])]
+    for m, nxt in zip(merges, st[1:]):
+        assert (m.Ho, m.Wo, m.N) == (nxt["spec"].H, nxt["spec"].W, nxt["spec"].C)
+    return dict(wl, image=(s0.B, s0.H * 4, s0.W * 4), embed=embed, merges=merges)
+
+
 def keep_count(nW, keep_ratio):
     return int(min(max(np.floor(keep_ratio * nW + 0.5), 0), nW))
 

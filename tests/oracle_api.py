@@ -206,3 +206,36 @@ def uniform_block(inp, x, branch, shift=None):
     rc = lib().ub_forward(C.byref(P), _p(x, _FP), _p(y, _FP))
     assert rc == 0
     return y
+
+
+# ---------------------------------------------------------------- layers between stages
+class DownDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("kind", "B", "H", "W", "C_in", "patch", "N", "act_bits", "weight_bits")] + \
+               [("ln_eps", C.c_float)]
+
+
+class DownParams(C.Structure):
+    _fields_ = [("w", _I8), ("s_w", _FP), ("bias", _FP), ("ln_gamma", _FP), ("ln_beta", _FP), ("a_in", QParam)]
+
+
+def downsample_forward(inp, x, want_taps=False, threads=8):
+    """inp: synth.DownInputs; x: [B,H,W,C_in] float32.  Returns (out, codes or None, acc or None)."""
+    sp = inp.spec
+    d = DownDesc(sp.kind, sp.B, sp.H, sp.W, sp.C_in, sp.patch, sp.N, sp.act_bits, sp.weight_bits, sp.ln_eps)
+    keep = [np.ascontiguousarray(inp.w, dtype=np.int8), np.ascontiguousarray(inp.s_w, dtype=np.float32),
+            None if inp.bias is None else np.ascontiguousarray(inp.bias, dtype=np.float32),
+            np.ascontiguousarray(inp.ln_gamma, dtype=np.float32), np.ascontiguousarray(inp.ln_beta, dtype=np.float32)]
+    pr = DownParams(_p(keep[0], _I8), _p(keep[1], _FP), _p(keep[2], _FP) if keep[2] is not None else None,
+                    _p(keep[3], _FP), _p(keep[4], _FP), QParam(inp.a_in[0], inp.a_in[1]))
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    assert x.shape == (sp.B, sp.H, sp.W, sp.C_in)
+    tokens = sp.B * sp.Ho * sp.Wo
+    out = np.empty((sp.B, sp.Ho, sp.Wo, sp.N), dtype=np.float32)
+    codes = np.empty((tokens, sp.K), dtype=np.int8) if want_taps else None
+    acc = np.empty((tokens, sp.N), dtype=np.int32) if want_taps else None
+    L = lib()
+    L.orc_downsample_forward.argtypes = [C.c_void_p, C.c_void_p, _FP, _FP, C.c_void_p, C.c_void_p, C.c_int32]
+    rc = L.orc_downsample_forward(C.byref(d), C.byref(pr), _p(x, _FP), _p(out, _FP),
+                                  codes.ctypes.data if want_taps else None, acc.ctypes.data if want_taps else None, threads)
+    assert rc == 0, rc
+    return out, codes, acc

@@ -1,0 +1,159 @@
+"""GPU parity of the layers between stages (patch embedding, patch merging) and of a whole backbone
+run as one chain: patch embedding, four stages through mixaq_stage_forward, patch merging between them."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_19131_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import oracle_api as O
+    from paper_2507_19131_amd import binding as M
+
+
+class GpuDown:
+    def __init__(self, inp):
+        self.inp = inp
+        self.params = M.downsample_to_device(inp)
+        self.h = M.mixaq_downsample_create(M.make_downsample_desc(inp.spec), self.params)
+
+    def close(self):
+        if self.h is not None:
+            M.mixaq_downsample_destroy(self.h)
+            self.h = None
+
+    def forward(self, x, taps=False):
+        sp = self.inp.spec
+        y = torch.full((sp.B, sp.Ho, sp.Wo, sp.N), float("nan"), dtype=torch.float32, device=x.device)
+        if not taps:
+            return M.mixaq_downsample_forward(self.h, x, y), None, None
+        codes = torch.zeros((sp.B * sp.Ho * sp.Wo, sp.K), dtype=torch.int8, device=x.device)
+        acc = torch.zeros((sp.B * sp.Ho * sp.Wo, sp.N), dtype=torch.int32, device=x.device)
+        M.mixaq_downsample_forward_taps(self.h, x, y, codes, acc)
+        return y, codes, acc
+
+
+CASES = [
+    # kind, B, H, W, C_in, N, bits, wbits
+    (0, 1, 64, 96, 3, 96, 8, 8),
+    (0, 2, 50, 45, 3, 96, 4, 4),        # sizes that are not multiples of the patch
+    (1, 1, 28, 42, 96, 192, 8, 8),
+    (1, 2, 15, 21, 192, 384, 4, 4),     # odd sizes: zero padding before the LayerNorm
+    (1, 1, 14, 14, 384, 768, 6, 8),
+]
+
+
+@pytest.mark.parametrize("kind,B,H,W,C_in,N,bits,wbits", CASES)
+def test_downsample_matches_oracle(kind, B, H, W, C_in, N, bits, wbits):
+    sp = synth.DownSpec(kind, B, H, W, C_in, N, act_bits=bits, weight_bits=wbits)
+    inp = synth.make_downsample_inputs(sp, 100 + kind)
+    if kind == 0:
+        x_np = synth.make_image(B, H, W, 50)
+    else:
+        x_np = synth.make_feature_map(synth.BlockSpec(B, H, W, C_in, C_in // 32), 51, blobs=True)
+    print("downsample case", kind, B, H, W, C_in, N, bits, wbits, flush=True)
+    gd = GpuDown(inp)
+    try:
+        y, codes, acc = gd.forward(torch.from_numpy(x_np).cuda(), taps=True)
+        y2, _, _ = gd.forward(torch.from_numpy(x_np).cuda())
+        torch.cuda.synchronize()
+    finally:
+        gd.close()
+    oy, ocodes, oacc = O.downsample_forward(inp, x_np, want_taps=True, threads=16)
+    assert np.array_equal(codes.cpu().numpy(), ocodes)
+    assert np.array_equal(acc.cpu().numpy(), oacc)
+    yn = y.cpu().numpy()
+    assert not np.isnan(yn).any()
+    rms = float(np.sqrt(np.mean(oy.astype(np.float64) ** 2)))
+    assert float(np.max(np.abs(yn.astype(np.float64) - oy))) <= 1e-3 * rms
+    assert np.array_equal(yn, oy)
+    assert torch.equal(y, y2)
+
+
+def test_downsample_error_paths():
+    sp = synth.DownSpec(1, 1, 14, 14, 96, 192)
+    inp = synth.make_downsample_inputs(sp, 7)
+    params = M.downsample_to_device(inp)
+    d = M.make_downsample_desc(sp)
+    d.N = 100
+    with pytest.raises(M.MixaqError) as e:
+        M.mixaq_downsample_create(d, params)
+    assert e.value.code == -2
+    d = M.make_downsample_desc(sp)
+    d.act_bits = 1
+    with pytest.raises(M.MixaqError) as e:
+        M.mixaq_downsample_create(d, params)
+    assert e.value.code == -3
+    d = M.make_downsample_desc(sp)
+    d.kind = 2
+    with pytest.raises(M.MixaqError) as e:
+        M.mixaq_downsample_create(d, params)
+    assert e.value.code == -2
+    assert M.mixaq_downsample_out_shape(M.make_downsample_desc(synth.DownSpec(1, 1, 15, 21, 96, 192))) == (8, 11, 384)
+
+
+def test_config4_backbone_chain():
+    """BASELINE config 4: Swin-T backbone on an 800x1344 image, W4A4 with 2-bit low windows, keep ratio 0.5
+    in every pair; the GPU chain against the oracle chain, bit for bit at every stage boundary."""
+    bb = synth.backbone("cfg4")
+    B, Hi, Wi = bb["image"]
+    img = synth.make_image(B, Hi, Wi, bb["seed"])
+    seed = bb["seed"]
+    embed = synth.make_downsample_inputs(bb["embed"], seed + 1)
+    merges = [synth.make_downsample_inputs(m, seed + 2 + i) for i, m in enumerate(bb["merges"])]
+    stage_inputs = [[synth.make_block_inputs(st["spec"], seed + 100 * si + 10 * i, ranges=bb.get("ranges"))
+                     for i, _ in enumerate(st["shifts"])] for si, st in enumerate(bb["stages"])]
+    keep = bb["keep"][0]
+    dev = torch.device("cuda:0")
+    # ---- GPU chain
+    boundaries_gpu = []
+    cur = torch.from_numpy(img).to(dev)
+    for si, st in enumerate(bb["stages"]):
+        gd = GpuDown(embed if si == 0 else merges[si - 1])
+        try:
+            cur, _, _ = gd.forward(cur)
+            torch.cuda.synchronize()
+        finally:
+            gd.close()
+        boundaries_gpu.append(cur.cpu().numpy())
+        spec = st["spec"]
+        blocks = []
+        for inp, shift in zip(stage_inputs[si], st["shifts"]):
+            sh, br = M.to_device(inp)
+            blocks.append((M.mixaq_block_create(M.make_desc(spec, shift), sh, br), sh, br))
+        try:
+            ws = M.alloc_workspace(blocks[0][0])
+            y, tmp = torch.empty_like(cur), torch.empty_like(cur)
+            scores = torch.empty((spec.B, spec.nW), dtype=torch.float64, device=dev)
+            perm = torch.empty((spec.B, spec.nW), dtype=torch.int32, device=dev)
+            k = synth.keep_count(spec.nW, keep)
+            n_pairs = (len(blocks) + 1) // 2
+            M.mixaq_stage_forward([b[0] for b in blocks], cur, [k] * n_pairs, None, y, tmp, scores, perm, ws)
+            torch.cuda.synchronize()
+            cur = y
+        finally:
+            for b in blocks:
+                M.mixaq_block_destroy(b[0])
+        boundaries_gpu.append(cur.cpu().numpy())
+        print("gpu stage", si, "done", flush=True)
+    # ---- oracle chain
+    cur_o = img
+    bi = 0
+    for si, st in enumerate(bb["stages"]):
+        cur_o, _, _ = O.downsample_forward(embed if si == 0 else merges[si - 1], cur_o, threads=16)
+        assert np.array_equal(boundaries_gpu[bi], cur_o), "layer before stage %d" % si
+        bi += 1
+        spec = st["spec"]
+        k = synth.keep_count(spec.nW, keep)
+        perm_o = O.select_windows(O.score_windows(stage_inputs[si][0], cur_o), k)
+        for inp, shift in zip(stage_inputs[si], st["shifts"]):
+            cur_o, _ = O.block_forward(inp, cur_o, perm_o, k, shift, threads=16)
+        g = boundaries_gpu[bi]
+        rms = float(np.sqrt(np.mean(cur_o.astype(np.float64) ** 2)))
+        err = float(np.max(np.abs(g.astype(np.float64) - cur_o)))
+        print("stage", si, "max abs err", err, "rms", rms, "bit identical", np.array_equal(g, cur_o), flush=True)
+        assert not np.isnan(g).any()
+        assert err <= 1e-3 * rms
+        bi += 1

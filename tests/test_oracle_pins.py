@@ -425,3 +425,69 @@ def test_pruned_windows_are_forwarded_and_the_rest_unchanged():
     assert np.array_equal(ya, y2)
     yi, _ = O.block_forward(inp, x, perm2, 0, k_low=0)
     assert np.array_equal(yi, x)
+
+
+# ---------------------------------------------------------------- layers between stages
+def _ln64(v, g, b, eps):
+    m = v.mean(axis=-1, keepdims=True)
+    var = ((v - m) ** 2).mean(axis=-1, keepdims=True)
+    return (v - m) / np.sqrt(var + eps) * g + b
+
+
+def _merge_concat(x):
+    """Swin's patch merging gather written with numpy slicing (zero padding to even sizes)."""
+    B, H, W, Cc = x.shape
+    xp = np.pad(x, ((0, 0), (0, H % 2), (0, W % 2), (0, 0)))
+    return np.concatenate([xp[:, 0::2, 0::2], xp[:, 1::2, 0::2], xp[:, 0::2, 1::2], xp[:, 1::2, 1::2]], axis=-1)
+
+
+def _patches(img, P):
+    """Non-overlapping PxP patches flattened in (row, column, channel) order, zero padded."""
+    B, H, W, Cc = img.shape
+    ip = np.pad(img, ((0, 0), (0, -H % P), (0, -W % P), (0, 0)))
+    Ho, Wo = ip.shape[1] // P, ip.shape[2] // P
+    return ip.reshape(B, Ho, P, Wo, P, Cc).transpose(0, 1, 3, 2, 4, 5).reshape(B, Ho, Wo, P * P * Cc)
+
+
+@pytest.mark.parametrize("H,W", [(8, 12), (9, 11)])
+def test_patch_merging_against_numpy(H, W):
+    sp = synth.DownSpec(1, 2, H, W, 8, 32)
+    inp = synth.make_downsample_inputs(sp, 5)
+    x = np.random.default_rng(3).standard_normal((2, H, W, 8)).astype(np.float32)
+    out, codes, acc = O.downsample_forward(inp, x, want_taps=True, threads=2)
+    cat = _merge_concat(x.astype(np.float64)).reshape(-1, sp.K)
+    assert out.shape == (2, (H + 1) // 2, (W + 1) // 2, 32)
+    ln = _ln64(cat, inp.ln_gamma.astype(np.float64), inp.ln_beta.astype(np.float64), sp.ln_eps)
+    s, z = inp.a_in
+    # codes decode to the float64 LayerNorm within half a step (+ float32 rounding) inside the clip range
+    lo, hi = s * (-128 - z), s * (127 - z)
+    inside = (ln > lo) & (ln < hi)
+    deq = s * (codes.astype(np.float64) - z)
+    assert np.max(np.abs(deq - ln)[inside]) <= 0.5 * s * (1 + 1e-4) + 1e-6
+    # integer sums: int64 matmul with the zero point removed
+    ref = (codes.astype(np.int64) - z) @ inp.w.astype(np.int64).T
+    assert np.array_equal(acc.astype(np.int64), ref)
+    # output: dequantized sums (no bias, no LayerNorm after the linear)
+    f = acc.astype(np.float64) * (np.float32(s) * inp.s_w).astype(np.float64)
+    assert np.max(np.abs(out.reshape(-1, 32) - f)) <= 1e-6 * max(1.0, np.abs(f).max())
+    # and close to the float layer it approximates
+    wf = inp.w.astype(np.float64) * inp.s_w.astype(np.float64)[:, None]
+    flt = ln @ wf.T
+    assert sqnr_db(flt, out.reshape(-1, 32)) >= 25.0           # 8-bit codes; the clip range cuts the largest LayerNorm outputs
+
+
+@pytest.mark.parametrize("H,W", [(16, 24), (18, 21)])
+def test_patch_embedding_against_numpy(H, W):
+    sp = synth.DownSpec(0, 1, H, W, 3, 32, patch=4)
+    inp = synth.make_downsample_inputs(sp, 6)
+    img = synth.make_image(1, H, W, 9)
+    out, codes, acc = O.downsample_forward(inp, img, want_taps=True, threads=2)
+    pt = _patches(img, 4).reshape(-1, 48)
+    s, z = inp.a_in
+    want = np.array([[_q_exact(v, s, z, 8) for v in row] for row in pt], dtype=np.int64)
+    assert np.array_equal(codes.astype(np.int64), want)        # gather order and quantizer, exactly
+    ref = (want - z) @ inp.w.astype(np.int64).T
+    assert np.array_equal(acc.astype(np.int64), ref)
+    f = ref.astype(np.float64) * (np.float32(s) * inp.s_w).astype(np.float64) + inp.bias.astype(np.float64)
+    ln = _ln64(f, inp.ln_gamma.astype(np.float64), inp.ln_beta.astype(np.float64), sp.ln_eps)
+    assert np.max(np.abs(out.reshape(-1, 32) - ln)) <= 2e-5 * max(1.0, np.abs(ln).max())
