@@ -137,7 +137,6 @@ __global__ __launch_bounds__(256) void downsample_kernel(DsArgs A)
             acc[qd * 4 + 0] = t4.x; acc[qd * 4 + 1] = t4.y; acc[qd * 4 + 2] = t4.z; acc[qd * 4 + 3] = t4.w;
         }
         const v4i* wp = A.Wp + (size_t)nb * ksn * 64 + lane;
-#pragma unroll 4
         for (int ks = 0; ks < ksn; ++ks) acc = mfma32(wp[ks * 64], frag[ks * 64 + lane], acc);
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {

@@ -323,7 +323,6 @@ __global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
                 c1 = mfma32(w, b1[ks], c1);
             }
         } else {
-#pragma unroll 4
             for (int ks = 0; ks < ks_n; ++ks) {
                 v4i w = wp[ks * 64];
                 v4i x0 = *(const v4i*)(a0p + ks * 32), x1 = *(const v4i*)(a1p + ks * 32);
