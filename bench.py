@@ -64,6 +64,18 @@ def kernel_model(name, C, F, heads, n_windows):
     raise KeyError(name)
 
 
+def kernel_hbm_bytes(name, C, n_windows):
+    """Algorithmic HBM bytes of one launch of a fused kernel (the gather / scatter side of it): the window
+    kernel reads the map and writes the attention-output codes; the token kernel reads the shortcut and the
+    codes and writes the map."""
+    T = 49
+    if name == "window_ln1_qkv_attention":
+        return n_windows * (4 * T * C + T * C)
+    if name == "token_proj_ln2_ffn_scatter":
+        return n_windows * (4 * T * C + T * C + 4 * T * C)
+    return None
+
+
 def read_traffic(kernel):
     """HBM bytes per launch of `kernel` from the committed counter summary (profiles/), or None."""
     path = os.path.join(ROOT, "profiles", "cfg2_hbm_traffic.txt")
@@ -173,6 +185,10 @@ def main():
         if mfma_ops is not None:        # the same launch against the int8 MFMA peak
             t = mfma_ops / (avg_ms * 1e-3) / 1e12
             kernels[n].update(int8_tops=round(t, 3), frac_int8_mfma_peak=round(t / PEAK_INT8_TOPS, 5))
+        hb = kernel_hbm_bytes(n, C, n_win)
+        if hb is not None:              # ... and its gather / scatter traffic against the HBM peak
+            gbs = hb / (avg_ms * 1e-3) / 1e9
+            kernels[n].update(hbm_gbs=round(gbs, 1), frac_hbm_peak=round(gbs / PEAK_HBM_GBS, 5))
     per_step = {n: kernels[n]["avg_ms"] * kernels[n]["launches_per_step"] for n in kernels}
     dom = max(per_step, key=per_step.get)
     kd = kernels[dom]
