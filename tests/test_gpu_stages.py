@@ -115,3 +115,38 @@ def test_stage_entry_point_with_a_ratio_per_pair_and_pruning(fused):
         cur, _ = O.block_forward(inp, cur, perm_o, k_high[i // 2], shift, threads=16, k_low=k_low[i // 2])
     check(y_gpu, cur, perm_gpu, perm_o)
     assert np.array_equal(y_gpu, cur)
+
+
+def test_stage_on_a_side_stream_matches_the_default_stream():
+    """All work of a call is enqueued on the stream it is given: a stage run on a second stream (default
+    priority) while the default stream is kept busy gives the same bits."""
+    wl = synth.workload("cfg2")
+    st = wl["stages"][0]
+    spec = synth.BlockSpec(1, 60, 75, 96, 3)
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(synth.make_feature_map(spec, 88, blobs=True)).to(dev)
+    blocks = [gh.GpuBlock(synth.make_block_inputs(spec, 880 + i), shift) for i, shift in enumerate(st["shifts"])]
+    try:
+        k = synth.keep_count(spec.nW, 0.5)
+        outs = []
+        side = torch.cuda.Stream()
+        for stream in (None, side):
+            y, tmp = torch.full_like(x, float("nan")), torch.empty_like(x)
+            scores = torch.empty((spec.B, spec.nW), dtype=torch.float64, device=dev)
+            perm = torch.empty((spec.B, spec.nW), dtype=torch.int32, device=dev)
+            ws = M.alloc_workspace(blocks[0].blk)
+            torch.cuda.synchronize()
+            if stream is not None:
+                busy = torch.empty(1 << 26, device=dev)
+                for _ in range(8):
+                    busy.normal_()                                  # keeps the default stream occupied meanwhile
+            M.mixaq_stage_forward([gb.blk for gb in blocks], x, [k], None, y, tmp, scores, perm, ws, stream=stream)
+            if stream is not None:
+                stream.synchronize()
+                assert not torch.isnan(y).any()                     # complete as soon as ITS stream is
+            torch.cuda.synchronize()
+            outs.append(y.clone())
+        assert torch.equal(outs[0], outs[1])
+    finally:
+        for gb in blocks:
+            gb.close()
