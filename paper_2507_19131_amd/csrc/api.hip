@@ -28,7 +28,7 @@ int fail(int code, const char* fmt, ...)
 }
 // Cubic coefficients of the GELU remainder H(a) = (a/2) erfc(a / sqrt 2): on interval i the cubic in the
 // local coordinate d in [0,1) passes through H at the interval's ends and thirds.  Binary64 throughout,
-// one rounding to binary32 per coefficient.
+// one rounding to binary32 per coefficient (then the exact power-of-two factor of the scaled evaluation).
 void gelu_table(float* tab)
 {
     static const double lagrange[3][4] = {{-11.0, 18.0, -9.0, 2.0}, {18.0, -45.0, 36.0, -9.0}, {-9.0, 27.0, -27.0, 9.0}};
@@ -46,6 +46,8 @@ void gelu_table(float* tab)
             tab[4 * i + 1 + k] = (float)(acc * 0.5);
         }
     }
+    // the kernels work on values scaled by GELU_SCALE (see gelu_scaled): exact, a power of two
+    for (int e = 0; e < 4 * GELU_K; ++e) tab[e] *= GELU_SCALE;
 }
 }  // namespace mixaq
 
@@ -150,7 +152,8 @@ namespace {
 
 // packs W[N,K] (row-major int8) into MFMA A-operand order and builds the per-branch epilogue constants
 int prepare_linear(mixaq_block* blk, Linear& L, const int8_t* w_dev, const float* s_dev, int N, int K,
-                   const float* const bias_dev[2], const mixaq_qparam in_q[2], int weight_bits, bool reg_order)
+                   const float* const bias_dev[2], const mixaq_qparam in_q[2], int weight_bits, bool reg_order,
+                   float out_scale = 1.0f)   // a power of two folded into the epilogue constants (exact; see gelu_scaled)
 {
     std::vector<int8_t> w;
     std::vector<float> s, b;
@@ -196,7 +199,8 @@ int prepare_linear(mixaq_block* blk, Linear& L, const int8_t* w_dev, const float
         std::vector<float> m(N);
         std::vector<int> nc(N);
         for (int n = 0; n < N; ++n) {
-            m[n] = in_q[br].scale * s[n];
+            m[n] = (in_q[br].scale * s[n]) * out_scale;
+            b[n] *= out_scale;
             nc[n] = -in_q[br].zero_point * colsum[n];
         }
         if ((rc = upload(blk->owned, m, &L.m[br]))) return rc;
@@ -454,7 +458,7 @@ int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* 
     qi[0] = branch[0].a_proj_in; qi[1] = branch[1].a_proj_in; bias[0] = branch[0].b_proj; bias[1] = branch[1].b_proj;
     if ((rc = prepare_linear(b, b->proj, sh->w_proj, sh->s_proj, C, C, bias, qi, desc->weight_bits, false))) return bail(rc);
     qi[0] = branch[0].a_fc1_in; qi[1] = branch[1].a_fc1_in; bias[0] = branch[0].b_fc1; bias[1] = branch[1].b_fc1;
-    if ((rc = prepare_linear(b, b->fc1, sh->w_fc1, sh->s_fc1, F, C, bias, qi, desc->weight_bits, true))) return bail(rc);
+    if ((rc = prepare_linear(b, b->fc1, sh->w_fc1, sh->s_fc1, F, C, bias, qi, desc->weight_bits, true, GELU_SCALE))) return bail(rc);
     qi[0] = branch[0].a_fc2_in; qi[1] = branch[1].a_fc2_in; bias[0] = branch[0].b_fc2; bias[1] = branch[1].b_fc2;
     if ((rc = prepare_linear(b, b->fc2, sh->w_fc2, sh->s_fc2, C, F, bias, qi, desc->weight_bits, true))) return bail(rc);
     std::vector<float> tmp;
@@ -474,6 +478,7 @@ int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* 
         b->q_ao[br] = make_qdev(branch[br].a_proj_in, bits);
         b->q_fc1in[br] = make_qdev(branch[br].a_fc1_in, bits);
         b->q_fc2in[br] = make_qdev(branch[br].a_fc2_in, bits);
+        b->q_fc2in[br].inv_s /= GELU_SCALE;              // it quantizes the scaled GELU output (exact, a power of two)
         b->m2[br] = ((branch[br].a_q.scale * branch[br].a_k.scale) * (float)(1.0 / std::sqrt((double)HD))) * LOG2E_F;
         b->m_o[br] = branch[br].a_p.scale * branch[br].a_v.scale;
     }

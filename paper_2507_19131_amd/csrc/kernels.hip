@@ -257,7 +257,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& A, const Geom& G, int b
         float f2 = fmaf((float)a2, m.z, bs.z), f3 = fmaf((float)a3, m.w, bs.w);
         if (A.tap_acc && canon >= 0) *(int4*)(A.tap_acc + (size_t)canon * N + n0) = make_int4(a0, a1, a2, a3);
         if (EPI == EPI_QKV || EPI == EPI_FC1) {
-            if (EPI == EPI_FC1) { f0 = gelu_pinned(f0, gelu_lds); f1 = gelu_pinned(f1, gelu_lds); f2 = gelu_pinned(f2, gelu_lds); f3 = gelu_pinned(f3, gelu_lds); }
+            if (EPI == EPI_FC1) { f0 = gelu_scaled(f0, gelu_lds); f1 = gelu_scaled(f1, gelu_lds); f2 = gelu_scaled(f2, gelu_lds); f3 = gelu_scaled(f3, gelu_lds); }
             const QDev& q = A.q[branch][EPI == EPI_QKV ? n0 / G.C : 0];
             int code = pack4(quant_code(f0, q), quant_code(f1, q), quant_code(f2, q), quant_code(f3, q));
             *(int*)(A.out8 + (size_t)row * N + n0) = code;
@@ -964,10 +964,10 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(NH <= 4
             for (int qd = 0; qd < 4; ++qd) {
                 const int n0 = hb * 32 + qd * 8 + g * 4;
                 const float4 m = *(const float4*)(prm + PR::F1_M + n0), bs = *(const float4*)(prm + PR::F1_B + n0);
-                wd[qd] = pack4(quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 0], m.x, bs.x), gelu_lds), qg),
-                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 1], m.y, bs.y), gelu_lds), qg),
-                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 2], m.z, bs.z), gelu_lds), qg),
-                               quant_code(gelu_pinned(fmaf((float)acc[qd * 4 + 3], m.w, bs.w), gelu_lds), qg));
+                wd[qd] = pack4(quant_code(gelu_scaled(fmaf((float)acc[qd * 4 + 0], m.x, bs.x), gelu_lds), qg),
+                               quant_code(gelu_scaled(fmaf((float)acc[qd * 4 + 1], m.y, bs.y), gelu_lds), qg),
+                               quant_code(gelu_scaled(fmaf((float)acc[qd * 4 + 2], m.z, bs.z), gelu_lds), qg),
+                               quant_code(gelu_scaled(fmaf((float)acc[qd * 4 + 3], m.w, bs.w), gelu_lds), qg));
                 if (tap_ok) {
                     if (A.tap_acc_fc1) *(int4*)(A.tap_acc_fc1 + canon * F + n0) = make_int4(acc[qd * 4], acc[qd * 4 + 1], acc[qd * 4 + 2], acc[qd * 4 + 3]);
                     if (A.tap_g) *(int*)(A.tap_g + canon * F + n0) = wd[qd];
@@ -1178,10 +1178,10 @@ __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A
                 for (int qd = 0; qd < 4; ++qd) {
                     const int n0 = hb * 32 + qd * 8 + g * 4;
                     const float4 m = *(const float4*)(prm + PR::F1_M + n0), bs = *(const float4*)(prm + PR::F1_B + n0);
-                    wd[qd] = pack4(quant_code(gelu_pinned(fmaf((float)acc[rb][qd * 4 + 0], m.x, bs.x), gtab), qg),
-                                   quant_code(gelu_pinned(fmaf((float)acc[rb][qd * 4 + 1], m.y, bs.y), gtab), qg),
-                                   quant_code(gelu_pinned(fmaf((float)acc[rb][qd * 4 + 2], m.z, bs.z), gtab), qg),
-                                   quant_code(gelu_pinned(fmaf((float)acc[rb][qd * 4 + 3], m.w, bs.w), gtab), qg));
+                    wd[qd] = pack4(quant_code(gelu_scaled(fmaf((float)acc[rb][qd * 4 + 0], m.x, bs.x), gtab), qg),
+                                   quant_code(gelu_scaled(fmaf((float)acc[rb][qd * 4 + 1], m.y, bs.y), gtab), qg),
+                                   quant_code(gelu_scaled(fmaf((float)acc[rb][qd * 4 + 2], m.z, bs.z), gtab), qg),
+                                   quant_code(gelu_scaled(fmaf((float)acc[rb][qd * 4 + 3], m.w, bs.w), gtab), qg));
                     if (TAPS && valid[rb]) {
                         if (A.tap_acc_fc1) *(int4*)(A.tap_acc_fc1 + canon[rb] * F + n0) = make_int4(acc[rb][qd * 4], acc[rb][qd * 4 + 1], acc[rb][qd * 4 + 2], acc[rb][qd * 4 + 3]);
                         if (A.tap_g) *(int*)(A.tap_g + canon[rb] * F + n0) = wd[qd];

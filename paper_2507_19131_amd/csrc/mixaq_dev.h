@@ -72,21 +72,30 @@ __device__ __forceinline__ float exp2_pinned(float y, const PolyCoef& P)
 // 2^-GELU_LOG2K on [0,6) holds the cubic in d = fract(a * 2^GELU_LOG2K); beyond the last
 // interval the argument is held at its end.  The coefficient table (one float4 per interval)
 // lives in LDS; replicating it per lane group to spread the banks was measured and is no faster.
+//
+// The kernels evaluate it on SCALED values: xs = x * 2^GELU_LOG2K goes in, GELU(x) * 2^GELU_LOG2K
+// comes out, with the table's coefficients scaled by the same power of two.  A power-of-two
+// factor commutes with every binary32 rounding (no overflow or underflow is near), so each
+// step is exactly 2^GELU_LOG2K times the unscaled step and the codes are the same bit for bit,
+// provided the caller folds the factor into what surrounds the call: the dequantization that
+// produces xs uses (2^GELU_LOG2K * m, 2^GELU_LOG2K * bias), the quantizer that consumes the
+// result uses inv_s / 2^GELU_LOG2K.  This saves the multiply that would form the table index.
 constexpr int GELU_LOG2K = 4;
 constexpr int GELU_K = 6 << GELU_LOG2K;                       // intervals on [0,6)
+constexpr float GELU_SCALE = (float)(1 << GELU_LOG2K);
 __device__ __forceinline__ void gelu_stage_table(float4* lds, const float4* tab, int tid, int nthreads)
 {
     for (int e = tid; e < GELU_K; e += nthreads) lds[e] = tab[e];
 }
-__device__ __forceinline__ float gelu_pinned(float x, const float4* lds)
+__device__ __forceinline__ float gelu_scaled(float xs, const float4* lds)
 {
-    const float u = fminf(fabsf(x) * (float)(1 << GELU_LOG2K), (float)GELU_K * 0x1.fffffep-1f);
+    const float u = fminf(fabsf(xs), (float)GELU_K * 0x1.fffffep-1f);
     const float d = __builtin_amdgcn_fractf(u);
     const float4 c = lds[(int)u];
     float h = fmaf(c.w, d, c.z);
     h = fmaf(h, d, c.y);
     h = fmaf(h, d, c.x);
-    return fmaxf(x, 0.0f) - h;
+    return fmaxf(xs, 0.0f) - h;
 }
 
 // D[32x32] += A[32 x 32k] * B[32k x 32]; lane l supplies row (A) / column (B) l%32 and
