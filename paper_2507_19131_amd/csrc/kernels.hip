@@ -277,6 +277,9 @@ __device__ __forceinline__ void epilogue(const GemmArgs& A, const Geom& G, int b
     }
 }
 
+#ifndef GEMM_RING
+#define GEMM_RING 4
+#endif
 template <int KS, int EPI>      // KS = K/32 when the activation fragments fit in registers, 0 = stream them
 __global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
 {
@@ -322,12 +325,22 @@ __global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
                 c0 = mfma32(w, b0[ks], c0);
                 c1 = mfma32(w, b1[ks], c1);
             }
-        } else {
-            for (int ks = 0; ks < ks_n; ++ks) {
-                v4i w = wp[ks * 64];
-                v4i x0 = *(const v4i*)(a0p + ks * 32), x1 = *(const v4i*)(a1p + ks * 32);
-                c0 = mfma32(w, x0, c0);
-                c1 = mfma32(w, x1, c1);
+        } else {                      // long K (a multiple of 8 slabs): operands stream from L2 through a ring, D slabs ahead
+            constexpr int D = GEMM_RING;
+            v4i rw[D], r0[D], r1[D];
+#pragma unroll
+            for (int d = 0; d < D; ++d) { rw[d] = wp[d * 64]; r0[d] = *(const v4i*)(a0p + d * 32); r1[d] = *(const v4i*)(a1p + d * 32); }
+#pragma unroll 1
+            for (int k0 = 0; k0 < ks_n; k0 += D) {
+                const int kn = k0 + D < ks_n ? k0 + D : k0;              // the last turn re-reads its own slabs (unused)
+#pragma unroll
+                for (int d = 0; d < D; ++d) {
+                    const v4i w = rw[d], x0 = r0[d], x1 = r1[d];
+                    const int ks = kn + d;
+                    rw[d] = wp[ks * 64]; r0[d] = *(const v4i*)(a0p + ks * 32); r1[d] = *(const v4i*)(a1p + ks * 32);
+                    c0 = mfma32(w, x0, c0);
+                    c1 = mfma32(w, x1, c1);
+                }
             }
         }
         epilogue<EPI>(A, G, branch, row0 + j, nb, g, c0, pix[0], canon[0], gelu_lds);

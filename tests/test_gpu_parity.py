@@ -182,3 +182,39 @@ def test_forward_from_scores_matches_oracle(C, heads, shift, kh_frac, kl_frac):
     assert np.array_equal(perm_out.cpu().numpy(), o_perm)
     oy, _ = O.block_forward(inp, x, o_perm, kh, k_low=None if kl < 0 else kl)
     assert np.array_equal(y.cpu().numpy(), oy)
+
+
+def test_equal_scores_are_ordered_by_window_index():
+    """Windows with exactly equal scores (here: windows that are zero everywhere, and two copies of one
+    window) must be ranked by their index on both sides; the block output follows."""
+    spec, inp, x, _ = _case(2, 35, 42, 96, 3, 3, 0.5, 61, blobs=True)
+    x = x.copy()
+    x[:, 7:21, 14:35, :] = 0.0                       # six whole windows of the un-shifted grid, score 0
+    x[:, 28:35, 0:7, :] = x[:, 0:7, 0:7, :]          # window 20 repeats window 0
+    for k in (3, 12, 26):                            # the cut falls before, inside and after the tied windows
+        print("tie case k_high", k, flush=True)
+        res = gh.compare_block(inp, x, k, taps=("a_proj_in",))
+        print(res, flush=True)
+        gh.assert_parity(res)
+        assert res["y_internal_select_equal"]
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_random_shapes_and_precisions(case):
+    """Seeded random draws of batch, map size (padding in both directions), width, shift, keep ratio and bit
+    widths: every tap and the output against the oracle."""
+    rng = np.random.default_rng(9000 + case)
+    C, heads = [(96, 3), (128, 4), (192, 6), (256, 8)][int(rng.integers(0, 4))]
+    B = int(rng.integers(1, 4))
+    H, W = int(rng.integers(14, 40)), int(rng.integers(14, 40))
+    shift = int(rng.integers(0, 2)) * 3
+    keep = float(rng.choice([0.0, 0.2, 0.5, 0.8, 1.0]))
+    hi = int(rng.integers(4, 9))
+    lo = int(rng.integers(2, hi + 1))
+    wbits = int(rng.choice([4, 8]))
+    spec, inp, x, k = _case(B, H, W, C, heads, shift, keep, 9100 + case, blobs=bool(rng.integers(0, 2)), bits=(hi, lo), wbits=wbits,
+                            mode=int(rng.integers(0, 2)))
+    print("random case", case, B, H, W, C, shift, keep, hi, lo, wbits, flush=True)
+    res = gh.compare_block(inp, x, k)
+    print(res, flush=True)
+    gh.assert_parity(res)
