@@ -150,3 +150,34 @@ def test_stage_on_a_side_stream_matches_the_default_stream():
     finally:
         for gb in blocks:
             gb.close()
+
+
+def test_config2_stage_call_as_the_benchmark_launches_it():
+    """BASELINE config 2 at full size through mixaq_stage_forward, the one call a benchmark step makes
+    (score, selection inside the first block's first kernel, list handed to the shifted block)."""
+    wl = synth.workload("cfg2")
+    st = wl["stages"][0]
+    spec = st["spec"]
+    x_np = synth.make_feature_map(spec, wl["seed"], blobs=wl["blobs"], outlier_channels=wl["outliers"])
+    inputs = [synth.make_block_inputs(spec, wl["seed"] + 10 * i) for i, _ in enumerate(st["shifts"])]
+    k = synth.keep_count(spec.nW, wl["keep"][0])
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(x_np).to(dev)
+    blocks = [gh.GpuBlock(inp, shift) for inp, shift in zip(inputs, st["shifts"])]
+    try:
+        y, tmp = torch.full_like(x, float("nan")), torch.empty_like(x)
+        scores = torch.empty((spec.B, spec.nW), dtype=torch.float64, device=dev)
+        perm = torch.empty((spec.B, spec.nW), dtype=torch.int32, device=dev)
+        for _ in range(3):                                          # repeated calls reuse workspace, scores and list
+            M.mixaq_stage_forward([gb.blk for gb in blocks], x, [k], None, y, tmp, scores, perm, blocks[0].ws)
+        torch.cuda.synchronize()
+        y_gpu, perm_gpu = y.cpu().numpy(), perm.cpu().numpy()
+    finally:
+        for gb in blocks:
+            gb.close()
+    perm_o = O.select_windows(O.score_windows(inputs[0], x_np), k)
+    cur = x_np
+    for inp, shift in zip(inputs, st["shifts"]):
+        cur, _ = O.block_forward(inp, cur, perm_o, k, shift, threads=16)
+    check(y_gpu, cur, perm_gpu, perm_o)
+    assert np.array_equal(y_gpu, cur)
