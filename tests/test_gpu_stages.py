@@ -181,3 +181,47 @@ def test_config2_stage_call_as_the_benchmark_launches_it():
         cur, _ = O.block_forward(inp, cur, perm_o, k, shift, threads=16)
     check(y_gpu, cur, perm_gpu, perm_o)
     assert np.array_equal(y_gpu, cur)
+
+
+def test_stage_call_can_be_captured_in_a_graph():
+    """The stage call allocates nothing and never synchronises, so a caller may capture it; every replay, with
+    eager work and synchronisations in between, reproduces the eager result."""
+    spec = synth.BlockSpec(2, 40, 47, 96, 3)
+    dev = torch.device("cuda:0")
+    xs = [torch.from_numpy(synth.make_feature_map(spec, 90 + i, blobs=True)).to(dev) for i in range(3)]
+    blocks = [gh.GpuBlock(synth.make_block_inputs(spec, 900 + i), shift) for i, shift in enumerate([0, 3])]
+    try:
+        k = synth.keep_count(spec.nW, 0.5)
+        x = xs[0].clone()
+        y, tmp = torch.empty_like(x), torch.empty_like(x)
+        scores = torch.empty((spec.B, spec.nW), dtype=torch.float64, device=dev)
+        perm = torch.empty((spec.B, spec.nW), dtype=torch.int32, device=dev)
+        ws = blocks[0].ws
+        handles = [gb.blk for gb in blocks]
+
+        def step():
+            M.mixaq_stage_forward(handles, x, [k], None, y, tmp, scores, perm, ws)
+        eager = []
+        for xi in xs:
+            x.copy_(xi)
+            step()
+            torch.cuda.synchronize()
+            eager.append(y.clone())
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()                                                  # warm-up on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for rep in range(2):
+            for xi, want in zip(xs, eager):
+                x.copy_(xi)                                         # eager work between the replays
+                y.fill_(float("nan"))
+                graph.replay()
+                torch.cuda.synchronize()
+                assert torch.equal(y, want), rep
+    finally:
+        for gb in blocks:
+            gb.close()
