@@ -1029,41 +1029,41 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(NH <= 4
 #ifndef TOKEN_RING
 #define TOKEN_RING(NH) ((NH) == 8 ? 8 : (NH) == 12 ? 12 : 6)   // weight fragments in flight per wave
 #endif
-template <int NH, bool TAPS>
+template <int NH, bool TAPS, int RB>   // RB = 32-row blocks per tile (2; 1 when the map has too few rows to fill the chip)
 __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A)
 {
     constexpr int C = NH * 32, KS = NH, HB = 4 * NH, F = 4 * C, NT = NH * 64, RING = TOKEN_RING(NH);
     static_assert(NH % RING == 0, "a chain is a whole number of ring turns");
     using PR = TokPrm<C>;
-    __shared__ v4i actf[2 * KS * 64];                                 // [row block][k slab][lane]
-    __shared__ v4i gs[2][NH * 2 * 64];                                // [buffer][hidden block of the chunk][row block][lane]
-    __shared__ double part[2][NH][64];
+    __shared__ v4i actf[RB * KS * 64];                                 // [row block][k slab][lane]
+    __shared__ v4i gs[2][NH * RB * 64];                                // [buffer][hidden block of the chunk][row block][lane]
+    __shared__ double part[2][NH][32 * RB];
     __shared__ float4 gtab[GELU_K];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, g = lane >> 5;
-    const int tile = blockIdx.x, row_base = tile * 64;
+    const int tile = blockIdx.x, row_base = tile * (32 * RB);
     const int branch = row_base >= G.base_lo ? 1 : 0;                 // a tile never straddles the regions: scalar
     const int nb = wave;
     const float* prm = A.params[branch];
     const int* prmi = (const int*)prm;
-    int pix[2];
-    bool valid[2];
-    size_t canon[2];
+    int pix[RB];
+    bool valid[RB];
+    size_t canon[RB];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
+    for (int rb = 0; rb < RB; ++rb) {
         const int row = row_base + rb * 32 + j;
         valid[rb] = branch ? (row - G.base_lo < G.rows_lo) : (row < G.rows_hi);
         pix[rb] = valid[rb] ? A.row_pix[row] : -1;
         canon[rb] = (TAPS && valid[rb]) ? (size_t)A.row_canon[row] : 0;
     }
     // stage the attention codes of the tile: piece p = (row r, 16-byte chunk q) -> fragment (r/32, q/2), lane (r%32, q%2)
-    for (int p = tid; p < 64 * (C / 16); p += NT) {
+    for (int p = tid; p < 32 * RB * (C / 16); p += NT) {
         const int r = p / (C / 16), q = p - r * (C / 16);
         actf[((r >> 5) * KS + (q >> 1)) * 64 + (q & 1) * 32 + (r & 31)] = *(const v4i*)(A.ao + (size_t)(row_base + r) * C + q * 16);
     }
     gelu_stage_table(gtab, A.gelu_tab, tid, NT);
-    float4 sc[2][4];
+    float4 sc[RB][4];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd)
             sc[rb][qd] = pix[rb] >= 0 ? *(const float4*)(A.x + (size_t)pix[rb] * C + nb * 32 + qd * 8 + g * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -1074,7 +1074,7 @@ __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A
             const int4 t4 = *(const int4*)(prmi + off + qd * 8 + g * 4);
             acc[0][qd * 4 + 0] = t4.x; acc[0][qd * 4 + 1] = t4.y; acc[0][qd * 4 + 2] = t4.z; acc[0][qd * 4 + 3] = t4.w;
         }
-        acc[1] = acc[0];
+        if (RB == 2) acc[RB - 1] = acc[0];
     };
     v4i ring[RING];
     auto request = [&](const v4i* wp) {
@@ -1092,20 +1092,20 @@ __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A
                 const v4i wv = ring[d];
                 if (i + RING < n) ring[d] = wp[(i + RING) * 64];
                 acc[0] = mfma32(wv, b[(i * i_stride) * 64 + lane], acc[0]);
-                acc[1] = mfma32(wv, b[(rb_stride + i * i_stride) * 64 + lane], acc[1]);
+                if (RB == 2) acc[RB - 1] = mfma32(wv, b[(rb_stride + i * i_stride) * 64 + lane], acc[RB - 1]);
             }
         }
     };
     __syncthreads();                                                  // staged codes and table visible
-    float h[2][16];
+    float h[RB][16];
     {   // output projection + first residual
         const v4i* wp = A.Wproj + (size_t)nb * KS * 64 + lane;
         request(wp);
-        v16i acc[2];
+        v16i acc[RB];
         start(acc, PR::P_NC + nb * 32);
         chain(wp, actf, KS, 1, KS, acc);
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 const int n0 = nb * 32 + qd * 8 + g * 4;
@@ -1122,9 +1122,9 @@ __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A
     }
     request(A.W1 + (size_t)wave * KS * 64 + lane);                    // first FC1 chain, in flight during LN2
     {   // LN2: binary64 partial sums per (wave, token) through LDS, then normalise and quantize
-        float mean[2], rstd[2];
+        float mean[RB], rstd[RB];
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
+        for (int rb = 0; rb < RB; ++rb) {
             double s = 0.0;
 #pragma unroll
             for (int r = 0; r < 16; r += 4) s += ((double)h[rb][r] + (double)h[rb][r + 1]) + ((double)h[rb][r + 2] + (double)h[rb][r + 3]);
@@ -1133,7 +1133,7 @@ __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A
         }
         __syncthreads();                                              // also: every wave is done reading the attention codes
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
+        for (int rb = 0; rb < RB; ++rb) {
             double tot = 0.0;
 #pragma unroll
             for (int w2 = 0; w2 < NH; ++w2) tot += part[0][w2][rb * 32 + j];
@@ -1151,7 +1151,7 @@ __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A
         __syncthreads();
         const QDev qa = A.q_fc1in[branch];
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
+        for (int rb = 0; rb < RB; ++rb) {
             double tot = 0.0;
 #pragma unroll
             for (int w2 = 0; w2 < NH; ++w2) tot += part[1][w2][rb * 32 + j];
@@ -1172,7 +1172,7 @@ __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A
         }
     }
     __syncthreads();
-    v16i acc2[2];
+    v16i acc2[RB];
     start(acc2, PR::F2_NC + nb * 32);
     const QDev qg = A.q_fc2in[branch];
 #pragma unroll 1
@@ -1180,12 +1180,12 @@ __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A
         const int hb = ch * NH + wave;
         {   // FC1 + GELU + quantize of hidden block hb
             const v4i* wp = A.W1 + (size_t)hb * KS * 64 + lane;
-            v16i acc[2];
+            v16i acc[RB];
             start(acc, PR::F1_NC + hb * 32);
             chain(wp, actf, KS, 1, KS, acc);
             request(A.W2 + ((size_t)nb * HB + ch * NH) * 64 + lane); // FC2 fragments of this chunk, in flight during the epilogue
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
+            for (int rb = 0; rb < RB; ++rb) {
                 int wd[4];
 #pragma unroll
                 for (int qd = 0; qd < 4; ++qd) {
@@ -1200,19 +1200,19 @@ __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A
                         if (A.tap_g) *(int*)(A.tap_g + canon[rb] * F + n0) = wd[qd];
                     }
                 }
-                gs[ch & 1][(wave * 2 + rb) * 64 + lane] = (v4i){wd[0], wd[1], wd[2], wd[3]};
+                gs[ch & 1][(wave * RB + rb) * 64 + lane] = (v4i){wd[0], wd[1], wd[2], wd[3]};
             }
         }
         __syncthreads();                                              // chunk ch of the hidden codes complete
         {   // FC2 over the chunk's NH hidden blocks
             const v4i* wp = A.W2 + ((size_t)nb * HB + ch * NH) * 64 + lane;
             const v4i* gb = gs[ch & 1];
-            chain(wp, gb, 1, 2, NH, acc2);
+            chain(wp, gb, 1, RB, NH, acc2);
             if (ch < 3) request(A.W1 + (size_t)(hb + NH) * KS * 64 + lane);
         }
     }
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {   // second residual + scatter
             const int n0 = nb * 32 + qd * 8 + g * 4;
@@ -1349,6 +1349,9 @@ void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
 #undef WIN_CASE
 }
 
+#ifndef TOKEN_STREAM_SMALL
+#define TOKEN_STREAM_SMALL 128
+#endif
 #ifndef TOKEN_STREAM_FROM
 #define TOKEN_STREAM_FROM 12         // NH from which the streaming 64-row form is used (measured: the 32-row form wins below)
 #endif
@@ -1360,9 +1363,16 @@ void launch_token(const Geom& G, const TokArgs& A, hipStream_t st)
     if (A.taps) hipLaunchKernelGGL((token_kernel<NH, true>), dim3(G.rows_total / 32), dim3(NH * 64), 0, st, G, A); \
     else hipLaunchKernelGGL((token_kernel<NH, false>), dim3(G.rows_total / 32), dim3(NH * 64), 0, st, G, A);      \
     break
-#define STREAM_CASE(NH)                                                                                                  \
-    if (A.taps) hipLaunchKernelGGL((token_stream_kernel<NH, true>), dim3(G.rows_total / 64), dim3(NH * 64), 0, st, G, A); \
-    else hipLaunchKernelGGL((token_stream_kernel<NH, false>), dim3(G.rows_total / 64), dim3(NH * 64), 0, st, G, A);      \
+    // few rows (less than one 64-row tile for every second CU): 32-row tiles, twice the workgroups
+    const bool small = G.rows_total / 64 <= TOKEN_STREAM_SMALL;
+#define STREAM_CASE(NH)                                                                                                             \
+    if (small) {                                                                                                                    \
+        if (A.taps) hipLaunchKernelGGL((token_stream_kernel<NH, true, 1>), dim3(G.rows_total / 32), dim3(NH * 64), 0, st, G, A);   \
+        else hipLaunchKernelGGL((token_stream_kernel<NH, false, 1>), dim3(G.rows_total / 32), dim3(NH * 64), 0, st, G, A);         \
+    } else {                                                                                                                        \
+        if (A.taps) hipLaunchKernelGGL((token_stream_kernel<NH, true, 2>), dim3(G.rows_total / 64), dim3(NH * 64), 0, st, G, A);   \
+        else hipLaunchKernelGGL((token_stream_kernel<NH, false, 2>), dim3(G.rows_total / 64), dim3(NH * 64), 0, st, G, A);         \
+    }                                                                                                                               \
     break
     if (NHr >= TOKEN_STREAM_FROM) {
         switch (NHr) {
