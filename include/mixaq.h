@@ -261,8 +261,8 @@ int mixaq_sample_ratios(int32_t n, double s_min, double s_max, double upper, con
                         size_t *n_used, double *ratios);
 
 /* Chooses between the two implementations of the forward call: the fused pair of
- * kernels (one workgroup per window for gather/LN1/QKV/attention, one per 32-row
- * tile for proj/LN2/FFN/scatter; the default where supported: C <= 256, mlp_ratio
+ * kernels (one workgroup per window for gather/LN1/QKV/attention, one per 32- or 64-row
+ * tile for proj/LN2/FFN/scatter; the default where supported: C <= 384, mlp_ratio
  * 4) and the seven-kernel path that handles every supported shape.  Both give the
  * same bits.  Enabling on an unsupported shape returns MIXAQ_E_SHAPE. */
 int mixaq_block_set_fused(mixaq_block *blk, int32_t enable);
