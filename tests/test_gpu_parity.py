@@ -218,3 +218,30 @@ def test_random_shapes_and_precisions(case):
     res = gh.compare_block(inp, x, k)
     print(res, flush=True)
     gh.assert_parity(res)
+
+
+@pytest.mark.parametrize("kind", ["zeros", "constant_tokens", "huge", "denormal", "one_hot"])
+def test_degenerate_inputs(kind):
+    """Inputs at the edges of the float arithmetic: zero variance (rstd = 1/sqrt(eps)), saturated quantizers,
+    binary32 denormals, a single non-zero channel."""
+    spec, inp, x, k = _case(1, 21, 30, 96, 3, 3, 0.5, 71)
+    rng = np.random.default_rng(72)
+    if kind == "zeros":
+        x = np.zeros_like(x)
+    elif kind == "constant_tokens":
+        x = np.repeat(rng.standard_normal(x.shape[:3] + (1,)).astype(np.float32), 96, axis=3)
+    elif kind == "huge":
+        x = (x * np.float32(3e4)).astype(np.float32)
+    elif kind == "denormal":
+        x = (x.astype(np.float64) * 1e-39).astype(np.float32)
+        assert np.any((x != 0) & (np.abs(x) < 1.1754944e-38))
+    else:
+        x = np.zeros_like(x)
+        x[..., 5] = rng.standard_normal(x.shape[:3]).astype(np.float32) * 10
+    print("degenerate input", kind, flush=True)
+    res = gh.compare_block(inp, np.ascontiguousarray(x), k)
+    print(res, flush=True)
+    assert res["perm_mismatch"] == 0 and res["y_nan"] == 0
+    for n in gh.INT_TAPS:
+        assert res[n] == 0, (n, res)
+    assert res["y_bit_identical"], res
