@@ -33,6 +33,8 @@ SMALL = [
     (1, 28, 35, 96, 3, 3, 0.5, 18, dict(bits=(6, 3))),                                # odd bit widths
     (2, 21, 21, 128, 4, 3, 0.6, 19, dict(bits=(5, 2), wbits=4)),                      # 2-bit low branch, 4-bit weights
     (1, 7, 7, 96, 3, 0, 1.0, 20, {}),                                                 # a single window
+    (1, 5, 6, 96, 3, 0, 0.0, 24, {}),                                                 # a map smaller than one window
+    (2, 3, 20, 128, 4, 0, 0.5, 25, {}),                                               # one row of windows, mostly padding
 ]
 
 
