@@ -260,11 +260,12 @@ int mixaq_bops_tera(double total_gmacs, double act_bits, double other_operand_bi
 int mixaq_sample_ratios(int32_t n, double s_min, double s_max, double upper, const double *uniforms, size_t n_uniforms,
                         size_t *n_used, double *ratios);
 
-/* Chooses between the two implementations of the forward call: the fused pair of
- * kernels (one workgroup per window for gather/LN1/QKV/attention, one per 32- or 64-row
- * tile for proj/LN2/FFN/scatter; the default where supported: C <= 384, mlp_ratio
- * 4) and the seven-kernel path that handles every supported shape.  Both give the
- * same bits.  Enabling on an unsupported shape returns MIXAQ_E_SHAPE. */
+/* Chooses between the two implementations of the forward call: the fused kernels (a window
+ * kernel for gather/LN1/QKV/attention, a token kernel per 32- or 64-row tile for
+ * proj/LN2/FFN/scatter: C <= 384, the token kernel with mlp_ratio 4; each is the default where it
+ * is supported) and the seven-kernel path that handles every supported shape.  Both give the
+ * same bits.  enable = 0 selects the seven-kernel path; enabling on a shape no fused kernel
+ * covers returns MIXAQ_E_SHAPE. */
 int mixaq_block_set_fused(mixaq_block *blk, int32_t enable);
 
 /* Measurement aid for benchmarks (not part of the paper's method): one forward

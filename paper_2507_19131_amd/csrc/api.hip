@@ -145,7 +145,8 @@ struct mixaq_block {
     const float4* gelu_tab = nullptr;            // cubic coefficients of the pinned GELU
     size_t ws_bytes = 0;
     int rows_max = 0;
-    bool fused = false;        // window + token kernels instead of the seven-kernel path
+    bool fused_window = false; // the window kernel instead of gather/LN1 + QKV + attention kernels
+    bool fused_token = false;  // the token kernel instead of proj + LN2 + FC1 + FC2 kernels
 };
 
 namespace {
@@ -303,52 +304,13 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, co
         scores = ws.scores;
     }
     // the fused window kernel ranks the windows itself when it is given scores; the other path selects first
-    const bool in_kernel_select = !perm && blk->fused;
+    const bool fw = blk->fused_window, ft = blk->fused_token;
+    const bool in_kernel_select = !perm && fw;
     if (!perm && !in_kernel_select) {
         mark(1);
         for (int r = 0; r < reps; ++r) launch_select(scores, d.B, blk->nW, 0, perm_out ? perm_out : ws.perm, st);
         perm = perm_out ? perm_out : ws.perm;
     }
-    if (!blk->fused) launch_bypass(G, perm, x, y, st);             // pruned windows (if any) are forwarded; the fused window kernel does it itself
-    if (blk->fused) {
-        WinArgs wa = {};
-        wa.x = x; wa.perm = perm; wa.scores = in_kernel_select ? scores : nullptr; wa.reverse = 0; wa.perm_out = perm_out ? perm_out : ws.perm;
-        wa.y = y; wa.eps = d.ln_eps; wa.Wqkv = blk->qkv.Wp; wa.bias2 = blk->bias2; wa.out = ws.ao;
-        wa.row_pix = ws.row_pix; wa.row_canon = ws.row_canon;
-        TokArgs ta = {};
-        ta.ao = ws.ao; ta.x = x; ta.y = y; ta.row_pix = ws.row_pix; ta.row_canon = ws.row_canon; ta.eps = d.ln_eps;
-        ta.Wproj = blk->proj.Wp; ta.W1 = blk->fc1.Wp_reg; ta.W2 = blk->fc2.Wp_reg;
-        for (int br = 0; br < 2; ++br) {
-            wa.gamma[br] = blk->ln_gamma[0][br]; wa.beta[br] = blk->ln_beta[0][br]; wa.q_in[br] = blk->q_in[br];
-            wa.m[br] = blk->qkv.m[br]; wa.bias[br] = blk->qkv.bias[br]; wa.negcorr[br] = blk->qkv.negcorr[br];
-            for (int k = 0; k < 3; ++k) wa.q_qkv[br][k] = blk->q_qkv[br][k];
-            wa.m2[br] = blk->m2[br]; wa.m_o[br] = blk->m_o[br]; wa.qp[br] = blk->q_p[br]; wa.qo[br] = blk->q_ao[br];
-            ta.params[br] = blk->tok_params[br];
-            ta.q_fc1in[br] = blk->q_fc1in[br]; ta.q_fc2in[br] = blk->q_fc2in[br];
-        }
-        wa.tap_a1 = tp.a_qkv_in; wa.tap_acc = tp.acc_qkv; wa.tap_qkv = tp.qkv; wa.tap_s = tp.acc_s; wa.tap_p = tp.p;
-        wa.tap_o = tp.acc_o; wa.tap_code = tp.a_proj_in;
-        ta.tap_acc_proj = tp.acc_proj; ta.tap_h = tp.h; ta.tap_a2 = tp.a_fc1_in; ta.tap_acc_fc1 = tp.acc_fc1;
-        ta.tap_g = tp.a_fc2_in; ta.tap_acc_fc2 = tp.acc_fc2; ta.tap_y = tp.y_win;
-        wa.poly = pinned_coefficients();
-        ta.gelu_tab = blk->gelu_tab;
-        wa.taps = ta.taps = taps != nullptr;
-        mark(9);
-        for (int r = 0; r < reps; ++r) launch_window(G, wa, st);
-        mark(10);
-        for (int r = 0; r < reps; ++r) launch_token(G, ta, st);
-        mark(-1);
-        HIP_TRY(hipGetLastError());
-        return MIXAQ_OK;
-    }
-    // gather + LN1 + quantize
-    LnArgs la = {};
-    la.perm = perm; la.src = x; la.eps = d.ln_eps; la.out = ws.a1; la.row_pix = ws.row_pix; la.row_canon = ws.row_canon;
-    la.tap = tp.a_qkv_in;
-    for (int br = 0; br < 2; ++br) { la.gamma[br] = blk->ln_gamma[0][br]; la.beta[br] = blk->ln_beta[0][br]; la.q[br] = blk->q_in[br]; }
-    mark(2);
-    for (int r = 0; r < reps; ++r) launch_ln_quant(G, la, true, st);
-    // QKV projection
     auto fill = [&](GemmArgs& a, const Linear& L, const int8_t* act) {
         a = GemmArgs{};
         a.A = act; a.Wp = L.Wp; a.K = L.K; a.N = L.N;
@@ -357,25 +319,72 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, co
         a.gelu_tab = blk->gelu_tab;
     };
     GemmArgs ga;
-    fill(ga, blk->qkv, ws.a1);
-    for (int br = 0; br < 2; ++br) for (int k = 0; k < 3; ++k) ga.q[br][k] = blk->q_qkv[br][k];
-    ga.out8 = ws.qkv; ga.tap_acc = tp.acc_qkv; ga.tap_code = tp.qkv;
-    mark(3);
-    for (int r = 0; r < reps; ++r) launch_gemm(G, ga, EPI_QKV, st);
-    // windowed attention
-    AttnArgs aa = {};
-    aa.qkv = ws.qkv; aa.perm = perm; aa.bias2 = blk->bias2; aa.out = ws.ao;
-    for (int br = 0; br < 2; ++br) { aa.m2[br] = blk->m2[br]; aa.m_o[br] = blk->m_o[br]; aa.qp[br] = blk->q_p[br]; aa.qo[br] = blk->q_ao[br]; }
-    aa.poly = pinned_coefficients();
-    aa.tap_s = tp.acc_s; aa.tap_p = tp.p; aa.tap_o = tp.acc_o; aa.tap_code = tp.a_proj_in;
-    mark(4);
-    for (int r = 0; r < reps; ++r) launch_attn(G, aa, st);
+    LnArgs la = {};
+    // ---- first half: gather + LN1 + quantize, QKV, windowed attention -> attention-output codes, row bookkeeping
+    if (fw) {
+        WinArgs wa = {};
+        wa.x = x; wa.perm = perm; wa.scores = in_kernel_select ? scores : nullptr; wa.reverse = 0; wa.perm_out = perm_out ? perm_out : ws.perm;
+        wa.y = y; wa.eps = d.ln_eps; wa.Wqkv = blk->qkv.Wp; wa.bias2 = blk->bias2; wa.out = ws.ao;
+        wa.row_pix = ws.row_pix; wa.row_canon = ws.row_canon;
+        for (int br = 0; br < 2; ++br) {
+            wa.gamma[br] = blk->ln_gamma[0][br]; wa.beta[br] = blk->ln_beta[0][br]; wa.q_in[br] = blk->q_in[br];
+            wa.m[br] = blk->qkv.m[br]; wa.bias[br] = blk->qkv.bias[br]; wa.negcorr[br] = blk->qkv.negcorr[br];
+            for (int k = 0; k < 3; ++k) wa.q_qkv[br][k] = blk->q_qkv[br][k];
+            wa.m2[br] = blk->m2[br]; wa.m_o[br] = blk->m_o[br]; wa.qp[br] = blk->q_p[br]; wa.qo[br] = blk->q_ao[br];
+        }
+        wa.tap_a1 = tp.a_qkv_in; wa.tap_acc = tp.acc_qkv; wa.tap_qkv = tp.qkv; wa.tap_s = tp.acc_s; wa.tap_p = tp.p;
+        wa.tap_o = tp.acc_o; wa.tap_code = tp.a_proj_in;
+        wa.poly = pinned_coefficients();
+        wa.taps = taps != nullptr;
+        mark(9);
+        for (int r = 0; r < reps; ++r) launch_window(G, wa, st);       // also forwards pruned windows
+    } else {
+        launch_bypass(G, perm, x, y, st);                              // pruned windows (if any) are forwarded
+        la.perm = perm; la.src = x; la.eps = d.ln_eps; la.out = ws.a1; la.row_pix = ws.row_pix; la.row_canon = ws.row_canon;
+        la.tap = tp.a_qkv_in;
+        for (int br = 0; br < 2; ++br) { la.gamma[br] = blk->ln_gamma[0][br]; la.beta[br] = blk->ln_beta[0][br]; la.q[br] = blk->q_in[br]; }
+        mark(2);
+        for (int r = 0; r < reps; ++r) launch_ln_quant(G, la, true, st);
+        fill(ga, blk->qkv, ws.a1);
+        for (int br = 0; br < 2; ++br) for (int k = 0; k < 3; ++k) ga.q[br][k] = blk->q_qkv[br][k];
+        ga.out8 = ws.qkv; ga.tap_acc = tp.acc_qkv; ga.tap_code = tp.qkv;
+        mark(3);
+        for (int r = 0; r < reps; ++r) launch_gemm(G, ga, EPI_QKV, st);
+        AttnArgs aa = {};
+        aa.qkv = ws.qkv; aa.perm = perm; aa.bias2 = blk->bias2; aa.out = ws.ao;
+        for (int br = 0; br < 2; ++br) { aa.m2[br] = blk->m2[br]; aa.m_o[br] = blk->m_o[br]; aa.qp[br] = blk->q_p[br]; aa.qo[br] = blk->q_ao[br]; }
+        aa.poly = pinned_coefficients();
+        aa.tap_s = tp.acc_s; aa.tap_p = tp.p; aa.tap_o = tp.acc_o; aa.tap_code = tp.a_proj_in;
+        mark(4);
+        for (int r = 0; r < reps; ++r) launch_attn(G, aa, st);
+    }
+    // ---- second half: projection + residual, LN2, FFN, second residual, scatter
+    if (ft) {
+        TokArgs ta = {};
+        ta.ao = ws.ao; ta.x = x; ta.y = y; ta.row_pix = ws.row_pix; ta.row_canon = ws.row_canon; ta.eps = d.ln_eps;
+        ta.Wproj = blk->proj.Wp; ta.W1 = blk->fc1.Wp_reg; ta.W2 = blk->fc2.Wp_reg;
+        for (int br = 0; br < 2; ++br) {
+            ta.params[br] = blk->tok_params[br];
+            ta.q_fc1in[br] = blk->q_fc1in[br]; ta.q_fc2in[br] = blk->q_fc2in[br];
+        }
+        ta.tap_acc_proj = tp.acc_proj; ta.tap_h = tp.h; ta.tap_a2 = tp.a_fc1_in; ta.tap_acc_fc1 = tp.acc_fc1;
+        ta.tap_g = tp.a_fc2_in; ta.tap_acc_fc2 = tp.acc_fc2; ta.tap_y = tp.y_win;
+        ta.gelu_tab = blk->gelu_tab;
+        ta.taps = taps != nullptr;
+        mark(10);
+        for (int r = 0; r < reps; ++r) launch_token(G, ta, st);
+        mark(-1);
+        HIP_TRY(hipGetLastError());
+        return MIXAQ_OK;
+    }
     // output projection + first residual
     fill(ga, blk->proj, ws.ao);
     ga.outf = ws.h; ga.x = x; ga.tap_acc = tp.acc_proj; ga.tap_f = tp.h;
     mark(5);
     for (int r = 0; r < reps; ++r) launch_gemm(G, ga, EPI_PROJ, st);
     // LN2 + quantize
+    la = LnArgs{};
+    la.eps = d.ln_eps; la.row_pix = ws.row_pix; la.row_canon = ws.row_canon;
     la.perm = nullptr; la.src = ws.h; la.out = ws.a2; la.tap = tp.a_fc1_in;
     for (int br = 0; br < 2; ++br) { la.gamma[br] = blk->ln_gamma[1][br]; la.beta[br] = blk->ln_beta[1][br]; la.q[br] = blk->q_fc1in[br]; }
     mark(6);
@@ -518,8 +527,9 @@ int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* 
         if ((rc = upload(b->owned, tab, &dev))) return bail(rc);
         b->gelu_tab = (const float4*)dev;
     }
-    b->fused = fused_supported(C, desc->mlp_ratio);
-    if (b->fused) {     // parameter blocks of the token kernel: device-to-device gathers of what was just uploaded
+    b->fused_window = fused_window_supported(C);
+    b->fused_token = fused_token_supported(C, desc->mlp_ratio);
+    if (b->fused_token) {     // parameter blocks of the token kernel: device-to-device gathers of what was just uploaded
         for (int br = 0; br < 2; ++br) {
             std::vector<float> blkp((size_t)8 * C + 3 * F);
             struct { const void* src; int n; } parts[11] = {
@@ -648,9 +658,11 @@ int mixaq_block_forward_taps(const mixaq_block* blk, const float* x, const int32
 int mixaq_block_set_fused(mixaq_block* blk, int32_t enable)
 {
     if (!blk) return fail(MIXAQ_E_NULL, "block is NULL");
-    if (enable && !fused_supported(blk->d.C, blk->d.mlp_ratio))
-        return fail(MIXAQ_E_SHAPE, "the fused kernels need C in {96,128,192,256} and mlp_ratio 4");
-    blk->fused = enable != 0;
+    const bool w_ok = fused_window_supported(blk->d.C), t_ok = fused_token_supported(blk->d.C, blk->d.mlp_ratio);
+    if (enable && !w_ok && !t_ok)
+        return fail(MIXAQ_E_SHAPE, "no fused kernel covers C = %d, mlp_ratio = %d", blk->d.C, blk->d.mlp_ratio);
+    blk->fused_window = enable != 0 && w_ok;
+    blk->fused_token = enable != 0 && t_ok;
     return MIXAQ_OK;
 }
 

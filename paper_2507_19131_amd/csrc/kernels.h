@@ -113,7 +113,8 @@ struct TokArgs {                     // fused token kernel (proj + LN2 + FFN + s
 };
 
 bool channels_supported(int C);
-bool fused_supported(int C, int mlp_ratio);
+bool fused_window_supported(int C);
+bool fused_token_supported(int C, int mlp_ratio);
 void launch_window(const Geom& G, const WinArgs& A, hipStream_t st);
 void launch_token(const Geom& G, const TokArgs& A, hipStream_t st);
 bool launch_score(const Geom& G, const float* x, int mode, float eps, const float* gm, const float* bt, double* scores,

@@ -542,27 +542,30 @@ __global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
 }
 
 // ------------------------------------------------------------------ fused window kernel
-// One workgroup per window slot, one wave per head (NH = C/32 waves):
+// One workgroup per window slot (HG = 1) or per half of a window's heads (HG = 2: few windows, or more heads
+// than a workgroup has waves; both halves repeat the gather + LN1 phase), one wave per head (NH waves):
 //   gather (shift folded into the index map) + LN1 + quantize, shared through LDS as MFMA
 //   fragments -> per head: q, k (transposed product, lane = token) and v (plain product, lane =
 //   dim) straight into operand registers -> attention core -> codes of the attention output.
 #ifndef WIN_WAVES_PER_EU
 #define WIN_WAVES_PER_EU 3
 #endif
-template <int NH>
+template <int NH, int HG>
 struct WinCfg {
-    // lanes per token in the LN phase: NH (3, 4, 6 or 8), so that the 49 tokens fit one pass with about
-    // three quarters of the lanes busy; a wave holds 64/LPT whole groups
+    // lanes per token in the LN phase: one per wave (3, 4, 6, 8 or 12), so that the 49 tokens fit one pass
+    // with about three quarters of the lanes busy; a wave holds 64/LPT whole groups
     static constexpr int LPT = NH;
     static constexpr int GPW = 64 / LPT;                             // groups (tokens) per wave
-    static constexpr int NV = NH * 32 / (4 * LPT);                   // float4 per lane = 8
+    static constexpr int NV = NH * HG * 32 / (4 * LPT);              // float4 per lane = 8 * HG
 };
 
-template <int NH, bool TAPS, bool SCORED>
-__global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAVES_PER_EU))) void window_kernel(Geom G, WinArgs A)
+template <int NH, bool TAPS, bool SCORED, int HG = 1>
+__global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 2 && NH <= 8) ? 2 : WIN_WAVES_PER_EU))) void window_kernel(Geom G, WinArgs A)
 {
-    constexpr int C = NH * 32, KS = NH, LPT = WinCfg<NH>::LPT, NV = WinCfg<NH>::NV, NT = NH * 64;
-    constexpr int GPW = WinCfg<NH>::GPW;
+    constexpr int NHT = NH * HG;                                         // heads of the block; this workgroup runs NH of them
+    constexpr int C = NHT * 32, KS = NHT, LPT = WinCfg<NH, HG>::LPT, NV = WinCfg<NH, HG>::NV, NT = NH * 64;
+    constexpr int GPW = WinCfg<NH, HG>::GPW;
+    const int widx = HG == 1 ? blockIdx.x : blockIdx.x / HG, hg = HG == 1 ? 0 : blockIdx.x % HG;
     static_assert(NH * GPW >= TOK, "one pass must cover the window");
     __shared__ v4i a1s[2 * KS * 64];                                     // LN1 codes as fragments [token block][k slab][lane]
     __shared__ __attribute__((aligned(16))) int csum[NH][HD];
@@ -572,14 +575,15 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
     // under the total order of the scores); otherwise it is given a slot and looks the window up.
     int branch = 0, row0 = 0, canon_slot = 0, w, bimg;
     if (SCORED) {
-        bimg = blockIdx.x / G.nW;
-        w = blockIdx.x - bimg * G.nW;
-    } else if ((int)blockIdx.x < G.n_slots) {
-        slot_info(G, blockIdx.x, branch, row0, canon_slot);
+        bimg = widx / G.nW;
+        w = widx - bimg * G.nW;
+    } else if (widx < G.n_slots) {
+        slot_info(G, widx, branch, row0, canon_slot);
         w = A.perm[canon_slot];
         bimg = canon_slot / G.nW;
     } else {                              // workgroups past the computed slots: pruned windows (Sec. 3.4), features forwarded
-        const int kept = G.k_hi + G.k_lo, q = blockIdx.x - G.n_slots, b = q / (G.nW - kept);
+        if (hg != 0) return;
+        const int kept = G.k_hi + G.k_lo, q = widx - G.n_slots, b = q / (G.nW - kept);
         const int wp = A.perm[b * G.nW + kept + (q - b * (G.nW - kept))];
         const int wr = wp / G.nWc, wc = wp - wr * G.nWc;
         for (int i = tid; i < TOK * (C / 4); i += NT) {
@@ -592,6 +596,12 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
             }
         }
         return;
+    }
+    // The rows that pad each region to whole tiles belong to no window: the first workgroup marks them
+    // (pixel -1, slot-major row -1) for the kernels of the seven-kernel path, which read the marks of every row.
+    if (blockIdx.x == 0) {
+        for (int r = G.rows_hi + tid; r < G.base_lo; r += NT) { A.row_pix[r] = -1; A.row_canon[r] = -1; }
+        for (int r = G.base_lo + G.rows_lo + tid; r < G.rows_total; r += NT) { A.row_pix[r] = -1; A.row_canon[r] = -1; }
     }
     int* a1w = (int*)a1s;
     // dword index of (token slot s, channel c with c%4==0) in the fragment layout (k = channel, natural order)
@@ -637,7 +647,7 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
         for (int k = 0; k < NH; ++k) rank += red[k];
         if (tid == 0) A.perm_out[(size_t)bimg * G.nW + rank] = w;
         if (rank >= G.k_hi + G.k_lo) {                                    // pruned (Sec. 3.4): forward the features
-            if (pix >= 0) {
+            if (pix >= 0 && hg == 0) {
                 float* dst = A.y + (size_t)pix * C;
 #pragma unroll
                 for (int k = 0; k < NV; ++k) *(float4*)(dst + (k * LPT + sub) * 4) = v[k];
@@ -667,11 +677,11 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
         }
     }
     __syncthreads();
-    const int head = wave;
+    const int head = hg * NH + wave;
     // Operand handling.  Up to eight heads the LN1 fragments of both token blocks and the weight
     // fragments of one output block sit in registers; beyond that the B operand is read from LDS
     // inside the chain and the weight fragments stream through a short ring.
-    constexpr bool HOIST = NH <= 8;
+    constexpr bool HOIST = KS <= 8;
     constexpr int RING = 6;
     v4i bf[2][HOIST ? KS : 1];
     if (HOIST) {
@@ -698,7 +708,7 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
     v4i qk[2][2];                                                        // [q|k][token block]
 #pragma unroll
     for (int which = 0; which < 2; ++which) {
-        const int nb = which * NH + head;
+        const int nb = which * NHT + head;
         const QDev qq = A.q_qkv[branch][which];
         const v4i* wp = A.Wqkv + (size_t)nb * KS * 64 + lane;
         auto start = [&](v16i& acc) {                                     // accumulators start at -zp * colsum
@@ -749,7 +759,7 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
     }
     v4i vt[2];
     {
-        const int nb = 2 * NH + head, n = nb * 32 + j;                   // this lane's output channel (dim j of the head)
+        const int nb = 2 * NHT + head, n = nb * 32 + j;                   // this lane's output channel (dim j of the head)
         const v4i* wp = A.Wqkv + (size_t)nb * KS * 64 + lane;
         const float m = A.m[branch][n], bs = A.bias[branch][n];
         const int nc = A.negcorr[branch][n];
@@ -804,10 +814,10 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(WIN_WAV
     }
     AttnCore core;
     core.poly = &A.poly;
-    core.bm = A.bias2 + ((size_t)(mask_type(G, w) * NH + head) * TOK) * 64;
+    core.bm = A.bias2 + ((size_t)(mask_type(G, w) * NHT + head) * TOK) * 64;
     core.m2 = A.m2[branch];
     core.qp = A.qp[branch];
-    const size_t tbase = ((size_t)canon_slot * NH + head) * TOK * TOK;
+    const size_t tbase = ((size_t)canon_slot * NHT + head) * TOK * TOK;
     core.tap_s = A.tap_s ? A.tap_s + tbase : nullptr;
     core.tap_p = A.tap_p ? A.tap_p + tbase : nullptr;
     v16i o[2];
@@ -1321,30 +1331,42 @@ void launch_gemm(const Geom& G, const GemmArgs& A, int epi, hipStream_t st)
     }
 }
 
-bool fused_supported(int C, int mlp_ratio) { return (C == 96 || C == 128 || C == 192 || C == 256 || C == 384) && mlp_ratio == 4; }
+// the window kernel (gather + LN1 + QKV + attention) and the token kernel (proj + LN2 + FFN + scatter) are chosen separately
+// (a window kernel for C = 768, two workgroups of twelve heads per window, was measured at 37.5 us against 42 us for the three
+// kernels it replaces on 24 windows, and the whole stage came out slower: not enabled)
+bool fused_window_supported(int C) { return C == 96 || C == 128 || C == 192 || C == 256 || C == 384; }
+bool fused_token_supported(int C, int mlp_ratio) { return (C == 96 || C == 128 || C == 192 || C == 256 || C == 384) && mlp_ratio == 4; }
 
+#ifndef WINDOW_SPLIT_SMALL
+#define WINDOW_SPLIT_SMALL 128       // C = 384: up to this many windows, two workgroups share a window's heads
+#endif
 void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
 {
     // every window gets a workgroup: with scores it finds its own rank (and may turn out pruned), otherwise
     // the computed slots come first and the pruned windows of the list after them
     const int n_wg = G.B * G.nW;
     if (n_wg == 0) return;
-    dim3 grid(n_wg);
-#define WIN_CASE(NH)                                                                                             \
-    if (A.scores) {                                                                                              \
-        if (A.taps) hipLaunchKernelGGL((window_kernel<NH, true, true>), grid, dim3(NH * 64), 0, st, G, A);      \
-        else hipLaunchKernelGGL((window_kernel<NH, false, true>), grid, dim3(NH * 64), 0, st, G, A);            \
-    } else {                                                                                                     \
-        if (A.taps) hipLaunchKernelGGL((window_kernel<NH, true, false>), grid, dim3(NH * 64), 0, st, G, A);     \
-        else hipLaunchKernelGGL((window_kernel<NH, false, false>), grid, dim3(NH * 64), 0, st, G, A);           \
-    }                                                                                                            \
+#define WIN_CASE(NH, HG)                                                                                               \
+    {                                                                                                                  \
+        const dim3 grid(n_wg * HG);                                                                                    \
+        if (A.scores) {                                                                                                \
+            if (A.taps) hipLaunchKernelGGL((window_kernel<NH, true, true, HG>), grid, dim3(NH * 64), 0, st, G, A);     \
+            else hipLaunchKernelGGL((window_kernel<NH, false, true, HG>), grid, dim3(NH * 64), 0, st, G, A);           \
+        } else {                                                                                                       \
+            if (A.taps) hipLaunchKernelGGL((window_kernel<NH, true, false, HG>), grid, dim3(NH * 64), 0, st, G, A);    \
+            else hipLaunchKernelGGL((window_kernel<NH, false, false, HG>), grid, dim3(NH * 64), 0, st, G, A);          \
+        }                                                                                                              \
+    }                                                                                                                  \
     break
     switch (G.C / 32) {
-        case 3: WIN_CASE(3);
-        case 4: WIN_CASE(4);
-        case 6: WIN_CASE(6);
-        case 8: WIN_CASE(8);
-        default: WIN_CASE(12);
+        case 3: WIN_CASE(3, 1);
+        case 4: WIN_CASE(4, 1);
+        case 6: WIN_CASE(6, 1);
+        case 8: WIN_CASE(8, 1);
+        case 12:
+            if (n_wg <= WINDOW_SPLIT_SMALL) { WIN_CASE(6, 2); }
+            WIN_CASE(12, 1);
+        default: break;
     }
 #undef WIN_CASE
 }

@@ -41,7 +41,7 @@ SMALL = [
 @pytest.mark.parametrize("fused", [True, False])
 @pytest.mark.parametrize("B,H,W,C,heads,shift,keep,seed,kw", SMALL)
 def test_block_matches_oracle(B, H, W, C, heads, shift, keep, seed, kw, fused):
-    """fused: the window + token kernels (C <= 384); otherwise the seven-kernel path."""
+    """fused: the window and token kernels (C <= 384); otherwise the seven-kernel path."""
     if fused and C > 384:
         pytest.skip("the fused kernels cover C <= 384")
     spec, inp, x, k = _case(B, H, W, C, heads, shift, keep, seed, **kw)
