@@ -197,6 +197,25 @@ def main():
     if "frac_int8_mfma_peak" in kd:
         roofline.update(int8_tops=kd["int8_tops"], frac_int8_mfma_peak=kd["frac_int8_mfma_peak"])
 
+    # The same step with the score taken after a LayerNorm (score_mode 1: the scoring LayerNorm's parameters are
+    # the high branch's LN1 here); only the score kernel differs, and with it which windows are selected.
+    d1 = M.make_desc(spec, stage["shifts"][0])
+    d1.score_mode = 1
+    sh1, br1 = M.to_device(inputs[0])
+    blocks_m1 = [M.mixaq_block_create(d1, sh1, br1)] + blocks[1:]
+
+    def step_m1():
+        return M.mixaq_stage_forward(blocks_m1, x, [k_high], None, bufs[0], bufs[1], scores, perm, ws)
+    for _ in range(args.warmup):
+        step_m1()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step_m1()
+    torch.cuda.synchronize()
+    ms_per_step_m1 = (time.perf_counter() - t0) * 1e3 / args.steps
+    M.mixaq_block_destroy(blocks_m1[0])
+
     windows_per_step = n_win * len(blocks)
     ops_per_step = 2 * macs_per_window(C) * windows_per_step
     value = windows_per_step / (ms_per_step * 1e-3)
@@ -223,7 +242,9 @@ def main():
                dtype="int8 (int32 accumulate, fp32 epilogues)", data="synthetic",
                config=dict(workload="cfg2: Swin-T stage-1 pair (regular + shifted block), B=1, 200x336x96 padded to 203x336, "
                                     "1392 windows, 3 heads, keep 0.5, A8/A4, W8", blocks_per_step=len(blocks),
-                           windows_per_step=windows_per_step, k_high=k_high),
+                           windows_per_step=windows_per_step, k_high=k_high, score_mode=0),
+               score_after_layernorm=dict(score_mode=1, ms_per_step=round(ms_per_step_m1, 5),
+                                          value=round(windows_per_step / (ms_per_step_m1 * 1e-3), 1)),
                int_tops=round(int_tops, 3), pct_int8_mfma_peak=round(100 * int_tops / PEAK_INT8_TOPS, 3),
                ms_per_block=round(ms_per_step / len(blocks), 5),
                roofline=roofline, kernels=kernels, cpu_baseline=cpu)
