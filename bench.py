@@ -4,10 +4,11 @@
 One step = one pass of the whole path over the Swin-T stage-1 pair at detection
 scale (BASELINE config 2): score the 1392 windows of a 200x336x96 map once,
 run the regular block and then the shifted block (A8 high / A4 low, int8
-per-channel weights); the first kernel of each block takes the selection (keep
-ratio 0.5) from the scores.  Inputs are seeded
-synthetic tensors already resident in HBM; block creation (weight packing) is
-outside the timed region.  Prints ONE JSON line.
+per-channel weights), all through one mixaq_stage_forward call: the first
+block takes the selection (keep ratio 0.5) from the scores inside its first
+kernel and leaves the list for the shifted block.  Inputs are seeded synthetic
+tensors already resident in HBM; block creation (weight packing) is outside the
+timed region.  Prints ONE JSON line.
 """
 import argparse
 import json
