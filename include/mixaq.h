@@ -25,10 +25,14 @@
  *     map is zero-padded at the bottom/right to multiples of the window and, when
  *     shift > 0, rolled by -shift before partitioning and back afterwards.
  *   - x and y must not overlap.
- *   - Integer codes live in int8 containers whatever the bit width; a b-bit
- *     quantizer clamps to [-2^(b-1), 2^(b-1)-1]:  q = clamp(rne(v/scale) + zp).
- *   - Supported shapes: window 7, head_dim = C/heads = 32, C a multiple of 32,
- *     shift in {0,..,6} (shift > 0 needs padded height and width >= 14).
+ *   - Integer codes live in int8 containers whatever the bit width.  A b-bit
+ *     quantizer is  q = clamp(rne(v * (1.0f/scale) + zp), -2^(b-1), 2^(b-1)-1):
+ *     1.0f/scale is rounded to binary32 once, the product and the sum with the
+ *     integer zero point are taken exactly, and the single rounding rne() goes
+ *     to the nearest integer, ties to the even code.
+ *   - Supported shapes: window 7, head_dim = C/heads = 32, C in {96, 128, 192,
+ *     256, 384, 512, 768, 1024}, mlp_ratio in 1..8, shift in {0,..,6} (shift > 0
+ *     needs padded height and width >= 14), at most 4096 windows per image.
  */
 #ifndef MIXAQ_H
 #define MIXAQ_H
@@ -133,7 +137,8 @@ int mixaq_score_windows(const mixaq_block *blk, const float *x, double *scores, 
  * order of decreasing score (ties: lower index first); the high group is the
  * first k_high entries, the low group the rest.  reverse != 0 inverts the order
  * of importance (worst-case window selection of the robustness study, Sec. 4.1).
- * k_high only takes part in validation: the list is the same for every split. */
+ * A score that is NaN counts as the least important value (in either direction), so perm is
+ * always a permutation.  k_high only takes part in validation: the list is the same for every split. */
 int mixaq_select_windows(const double *scores, int32_t B, int32_t nW, int32_t k_high,
                          int32_t reverse, int32_t *perm, void *stream);
 

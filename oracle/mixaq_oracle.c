@@ -188,6 +188,16 @@ int orc_select_windows(const double *scores, int32_t B, int32_t nW, int32_t k_hi
     return orc_select_windows3(scores, B, nW, k_high, nW - k_high, reverse, perm);
 }
 
+/* reading: the paper orders windows by their L2 norm and says nothing of scores that are not numbers
+ * (a window holding NaN; Inf under the scoring LayerNorm).  Such a score is outside the order; it is
+ * ranked behind every number, infinities included (ties among them by index), so that the list stays a
+ * permutation. */
+static double rank_key(double s, int reverse)
+{
+    if (isnan(s)) return reverse ? INFINITY : -INFINITY;
+    return s;
+}
+
 /* Selection with activation pruning (Sec. 3.4): the windows with the lowest scores are pruned,
  * the rest is split as before.  perm is the same sorted list; its first k_high entries are the high
  * group, the next k_low the low group, the remainder is pruned. */
@@ -200,11 +210,16 @@ int orc_select_windows3(const double *scores, int32_t B, int32_t nW, int32_t k_h
         const double *s = scores + (size_t)b * nW;
         int32_t *p = perm + (size_t)b * nW;
         for (int w = 0; w < nW; ++w) {
+            double sw = rank_key(s[w], reverse);
+            int nw = isnan(s[w]);
             int rank = 0;                         /* windows strictly ahead of w */
             for (int v = 0; v < nW; ++v) {
                 if (v == w) continue;
-                int ahead = reverse ? (s[v] < s[w]) : (s[v] > s[w]);
-                if (ahead || (s[v] == s[w] && v < w)) ++rank;
+                double sv = rank_key(s[v], reverse);
+                int nv = isnan(s[v]);
+                int ahead = reverse ? (sv < sw) : (sv > sw);
+                /* equal keys: a number goes before a NaN, otherwise the lower index first */
+                if (ahead || (sv == sw && (nv != nw ? nw : v < w))) ++rank;
             }
             p[rank] = w;                          /* the rank under a total order is a permutation */
         }

@@ -11,8 +11,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# MIXAQ_LIBRARY lets a developer point at another build of the same library
-_LIB_PATH = os.environ.get("MIXAQ_LIBRARY") or os.path.join(_HERE, "libmixaq.so")
+_LIB_PATH = os.path.join(_HERE, "libmixaq.so")
 _lib = None
 
 TOK = 49

@@ -42,45 +42,79 @@ int mixaq_bops_tera(double total_gmacs, double act_bits, double other_operand_bi
     return MIXAQ_OK;
 }
 
-int mixaq_sample_ratios(int32_t n, double s_min, double s_max, double upper, const double* uniforms, size_t n_uniforms,
-                        size_t* n_used, double* ratios)
+}  // extern "C"
+
+// Uniform-sum sampling (Algorithm 1 of the appendix) as an apportionment problem: `seats` tenths are
+// to be shared among n pairs in proportion to exponential weights (normalised exponentials are a flat
+// Dirichlet draw).  A draw whose largest share exceeds the cap is thrown away.  The accepted shares are
+// turned into whole seats by Hamilton's method: everyone gets the whole part of the share, and the seats
+// still free go, one at a time, to the largest fractional part not yet served (first index on ties).
+namespace {
+struct Apportion {
+    std::vector<double> weight, share;
+    std::vector<long> seat;
+    explicit Apportion(int n) : weight(n), share(n), seat(n) {}
+    // returns false when a share exceeds the cap
+    bool shares(long seats, long cap)
+    {
+        double total = 0.0;
+        for (double w : weight) total += w;
+        if (!(total > 0.0)) return false;
+        for (size_t i = 0; i < weight.size(); ++i) {
+            share[i] = weight[i] / total * (double)seats;
+            if (share[i] > (double)cap) return false;
+        }
+        return true;
+    }
+    void hamilton(long seats)
+    {
+        const size_t n = share.size();
+        std::vector<double> frac(n);
+        long given = 0;
+        for (size_t i = 0; i < n; ++i) {
+            seat[i] = (long)std::floor(share[i]);
+            frac[i] = share[i] - (double)seat[i];
+            given += seat[i];
+        }
+        for (; given < seats; ++given) {
+            size_t best = n;
+            for (size_t i = 0; i < n; ++i)
+                if (frac[i] >= 0.0 && (best == n || frac[i] > frac[best])) best = i;
+            if (best == n) break;                            // every pair served once: cannot happen, the fractions sum to the free seats
+            seat[best] += 1;
+            frac[best] = -1.0;                               // served
+        }
+    }
+};
+}  // namespace
+
+extern "C" int mixaq_sample_ratios(int32_t n, double s_min, double s_max, double upper, const double* uniforms, size_t n_uniforms,
+                                   size_t* n_used, double* ratios)
 {
     if (!uniforms || !ratios) return fail(MIXAQ_E_NULL, "uniforms or ratios is NULL");
     if (n < 1 || !(s_min >= 0.0) || !(s_max >= s_min) || !(upper > 0.0) || upper > 1.0)
         return fail(MIXAQ_E_SHAPE, "need n >= 1, 0 <= s_min <= s_max, 0 < upper <= 1");
-    const long Smin = std::lround(s_min * 10.0), Smax = std::lround(s_max * 10.0), U = std::lround(upper * 10.0);
-    if (Smax > (long)n * U) return fail(MIXAQ_E_SHAPE, "s_max exceeds n*upper: the bound could never be met");
-    size_t pos = 0;
+    const long lo = std::lround(s_min * 10.0), hi = std::lround(s_max * 10.0), cap = std::lround(upper * 10.0);
+    if (hi > (long)n * cap) return fail(MIXAQ_E_SHAPE, "s_max exceeds n*upper: the bound could never be met");
     if (n_uniforms < 1) return fail(MIXAQ_E_WORKSPACE, "no random numbers supplied");
-    long S = Smin + (long)std::floor(uniforms[pos++] * (double)(Smax - Smin + 1));
-    S = std::min(std::max(S, Smin), Smax);
-    std::vector<double> r(n);
-    for (;;) {                                           // rejection: every ratio at most the upper bound
-        if (pos + (size_t)n > n_uniforms) {
-            if (n_used) *n_used = pos;
-            return fail(MIXAQ_E_WORKSPACE, "ran out of random numbers after %zu (rejection sampling still running)", pos);
+    size_t next = 0;
+    const long seats = std::min(std::max(lo + (long)std::floor(uniforms[next++] * (double)(hi - lo + 1)), lo), hi);
+    Apportion ap(n);
+    bool accepted = false;
+    while (!accepted) {
+        if (n_uniforms - next < (size_t)n) {
+            if (n_used) *n_used = next;
+            return fail(MIXAQ_E_WORKSPACE, "ran out of random numbers after %zu (rejection sampling still running)", next);
         }
-        double sum = 0.0;
-        for (int i = 0; i < n; ++i) {                    // flat Dirichlet = normalised exponentials
-            double u = uniforms[pos++];
-            r[i] = -std::log(u > 0.0 ? u : 1e-300);
-            sum += r[i];
+        for (int i = 0; i < n; ++i) {
+            const double u = uniforms[next++];
+            ap.weight[i] = -std::log(u > 0.0 ? u : 1e-300);
         }
-        bool ok = sum > 0.0;
-        for (int i = 0; i < n && ok; ++i) { r[i] = r[i] / sum * (double)S; ok = r[i] <= (double)U; }
-        if (ok) break;
+        accepted = ap.shares(seats, cap);
     }
-    std::vector<long> R(n);
-    long acc = 0;
-    for (int i = 0; i < n; ++i) { R[i] = (long)std::floor(r[i]); acc += R[i]; }
-    long diff = S - acc;
-    std::vector<int> order(n);
-    std::iota(order.begin(), order.end(), 0);
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return (r[a] - (double)R[a]) > (r[b] - (double)R[b]); });
-    for (long k = 0; k < diff && k < n; ++k) R[order[k]] += 1;   // largest remainder method
-    for (int i = 0; i < n; ++i) ratios[i] = (double)R[i] / 10.0;
-    if (n_used) *n_used = pos;
+    ap.hamilton(seats);
+    for (int i = 0; i < n; ++i) ratios[i] = (double)ap.seat[i] / 10.0;
+    if (n_used) *n_used = next;
     return MIXAQ_OK;
 }
 
-}  // extern "C"

@@ -128,6 +128,22 @@ __global__ __launch_bounds__(256) void score_kernel(Geom G, const float* __restr
 // window is the number of windows ahead of it, which is a permutation, so perm[rank] = window
 // lists the windows by decreasing importance; the high group is the first k_hi entries.
 // A wave ranks four windows at once, its lanes stride over the candidates held in LDS.
+// A score that is not a number (a window holding NaN, or Inf under the scoring LayerNorm) is outside
+// the order: it is ranked behind every number (infinities included), so the ranks stay a permutation.
+// rank_key maps it to the infinity at the unimportant end; among equal keys a number goes first.
+__device__ __forceinline__ double rank_key(double s, int reverse)
+{
+    const double worst = reverse ? __longlong_as_double(0x7ff0000000000000LL) : __longlong_as_double(0xfff0000000000000LL);
+    return s != s ? worst : s;
+}
+// true when candidate v (raw score rv) is ranked before window w (raw score rw)
+__device__ __forceinline__ bool ranked_before(double rv, int v, double rw, int w, int reverse)
+{
+    const double sv = rank_key(rv, reverse), sw = rank_key(rw, reverse);
+    const bool nv = rv != rv, nw = rw != rw;
+    const bool ahead = reverse ? (sv < sw) : (sv > sw);
+    return ahead || (sv == sw && (nv != nw ? nw : v < w));
+}
 constexpr int RANK_WPB = 16;                          // windows ranked per workgroup (4 per wave)
 __global__ __launch_bounds__(256) void select_rank_kernel(const double* __restrict__ scores, int nW, int reverse,
                                                           int* __restrict__ perm)
@@ -150,19 +166,15 @@ __global__ __launch_bounds__(256) void select_rank_kernel(const double* __restri
     int rank[Q];
 #pragma unroll
     for (int q = 0; q < Q; ++q) { sw[q] = rsc[min(w0 + q, nW - 1)]; rank[q] = 0; }
-    const double nan = __longlong_as_double(0x7ff8000000000000LL);       // compares false: contributes nothing
     for (int v0 = lane; v0 < nW; v0 += 256) {
         double sv[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) { const int v = v0 + 64 * u; sv[u] = v < nW ? rsc[v] : nan; }
+        for (int u = 0; u < 4; ++u) { const int v = v0 + 64 * u; sv[u] = rsc[min(v, nW - 1)]; }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int v = v0 + 64 * u;
 #pragma unroll
-            for (int q = 0; q < Q; ++q) {
-                const bool ahead = reverse ? (sv[u] < sw[q]) : (sv[u] > sw[q]);
-                rank[q] += (ahead || (sv[u] == sw[q] && v < w0 + q)) ? 1 : 0;
-            }
+            for (int q = 0; q < Q; ++q) rank[q] += (v < nW && ranked_before(sv[u], v, sw[q], w0 + q, reverse)) ? 1 : 0;
         }
     }
 #pragma unroll
@@ -277,9 +289,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& A, const Geom& G, int b
     }
 }
 
-#ifndef GEMM_RING
-#define GEMM_RING 4
-#endif
+constexpr int GEMM_RING = 4;          // operand slabs in flight per wave in the long-K GEMM
 template <int KS, int EPI>      // KS = K/32 when the activation fragments fit in registers, 0 = stream them
 __global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
 {
@@ -325,21 +335,25 @@ __global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
                 c0 = mfma32(w, b0[ks], c0);
                 c1 = mfma32(w, b1[ks], c1);
             }
-        } else {                      // long K (a multiple of 8 slabs): operands stream from L2 through a ring, D slabs ahead
+        } else {                      // long K: operands stream from L2 through a ring, D slabs ahead
             constexpr int D = GEMM_RING;
             v4i rw[D], r0[D], r1[D];
 #pragma unroll
-            for (int d = 0; d < D; ++d) { rw[d] = wp[d * 64]; r0[d] = *(const v4i*)(a0p + d * 32); r1[d] = *(const v4i*)(a1p + d * 32); }
+            for (int d = 0; d < D; ++d) {                                // K may hold fewer than D slabs: re-read the last one (unused)
+                const int ks = min(d, ks_n - 1);
+                rw[d] = wp[ks * 64]; r0[d] = *(const v4i*)(a0p + ks * 32); r1[d] = *(const v4i*)(a1p + ks * 32);
+            }
 #pragma unroll 1
             for (int k0 = 0; k0 < ks_n; k0 += D) {
-                const int kn = k0 + D < ks_n ? k0 + D : k0;              // the last turn re-reads its own slabs (unused)
 #pragma unroll
                 for (int d = 0; d < D; ++d) {
                     const v4i w = rw[d], x0 = r0[d], x1 = r1[d];
-                    const int ks = kn + d;
+                    const int ks = min(k0 + D + d, ks_n - 1);            // past the end: the last slab again (unused)
                     rw[d] = wp[ks * 64]; r0[d] = *(const v4i*)(a0p + ks * 32); r1[d] = *(const v4i*)(a1p + ks * 32);
-                    c0 = mfma32(w, x0, c0);
-                    c1 = mfma32(w, x1, c1);
+                    if (k0 + d < ks_n) {                                 // wave-uniform: the last turn may be partial
+                        c0 = mfma32(w, x0, c0);
+                        c1 = mfma32(w, x1, c1);
+                    }
                 }
             }
         }
@@ -547,9 +561,7 @@ __global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
 //   gather (shift folded into the index map) + LN1 + quantize, shared through LDS as MFMA
 //   fragments -> per head: q, k (transposed product, lane = token) and v (plain product, lane =
 //   dim) straight into operand registers -> attention core -> codes of the attention output.
-#ifndef WIN_WAVES_PER_EU
-#define WIN_WAVES_PER_EU 3
-#endif
+constexpr int WIN_WAVES_PER_EU = 3;
 template <int NH, int HG>
 struct WinCfg {
     // lanes per token in the LN phase: one per wave (3, 4, 6, 8 or 12), so that the 49 tokens fit one pass
@@ -625,17 +637,15 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
     if (SCORED) {
         const double* sc = A.scores + (size_t)bimg * G.nW;
         const double sw = sc[w];
-        const double nan = __longlong_as_double(0x7ff8000000000000LL);
         int cnt = 0;
         for (int base = 0; base < G.nW; base += 8 * NT) {                // eight loads in flight per thread
             double sv[8];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) { const int u = base + tid + k * NT; sv[k] = u < G.nW ? sc[u] : nan; }
+            for (int k = 0; k < 8; ++k) { const int u = base + tid + k * NT; sv[k] = sc[min(u, G.nW - 1)]; }
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 const int u = base + tid + k * NT;
-                const bool ahead = A.reverse ? (sv[k] < sw) : (sv[k] > sw);
-                cnt += (ahead || (sv[k] == sw && u < w)) ? 1 : 0;
+                cnt += (u < G.nW && ranked_before(sv[k], u, sw, w, A.reverse)) ? 1 : 0;
             }
         }
 #pragma unroll
@@ -835,9 +845,7 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
 // Latency is hidden by issuing loads a phase ahead: the per-branch parameter block (epilogue
 // constants, LN2 affine) is staged in LDS once, weight fragments of the next MFMA chain are
 // requested before the current epilogue starts.
-#ifndef TOK_WAVES_PER_EU
-#define TOK_WAVES_PER_EU 4
-#endif
+constexpr int TOK_WAVES_PER_EU = 4;
 // word offsets inside the parameter block of one branch (see TokArgs::params)
 template <int C> struct TokPrm {
     static constexpr int F = 4 * C;
@@ -1036,13 +1044,11 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(NH <= 4
 // flight; the FFN is cut into four chunks of NH hidden blocks: FC1 + GELU + quantize of a chunk goes to
 // one of two LDS buffers, then FC2 accumulates that chunk, so the hidden activations never exist as
 // a whole.  Epilogue constants are read from the per-branch parameter block in global memory.
-#ifndef TOKEN_RING
-#define TOKEN_RING(NH) ((NH) == 8 ? 8 : (NH) == 12 ? 12 : 6)   // weight fragments in flight per wave
-#endif
+constexpr int token_ring(int NH) { return NH == 8 ? 8 : NH == 12 ? 12 : 6; }   // weight fragments in flight per wave
 template <int NH, bool TAPS, int RB>   // RB = 32-row blocks per tile (2; 1 when the map has too few rows to fill the chip)
 __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A)
 {
-    constexpr int C = NH * 32, KS = NH, HB = 4 * NH, F = 4 * C, NT = NH * 64, RING = TOKEN_RING(NH);
+    constexpr int C = NH * 32, KS = NH, HB = 4 * NH, F = 4 * C, NT = NH * 64, RING = token_ring(NH);
     static_assert(NH % RING == 0, "a chain is a whole number of ring turns");
     using PR = TokPrm<C>;
     __shared__ v4i actf[RB * KS * 64];                                 // [row block][k slab][lane]
@@ -1337,9 +1343,7 @@ void launch_gemm(const Geom& G, const GemmArgs& A, int epi, hipStream_t st)
 bool fused_window_supported(int C) { return C == 96 || C == 128 || C == 192 || C == 256 || C == 384; }
 bool fused_token_supported(int C, int mlp_ratio) { return (C == 96 || C == 128 || C == 192 || C == 256 || C == 384) && mlp_ratio == 4; }
 
-#ifndef WINDOW_SPLIT_SMALL
-#define WINDOW_SPLIT_SMALL 128       // C = 384: up to this many windows, two workgroups share a window's heads
-#endif
+constexpr int WINDOW_SPLIT_SMALL = 128;      // C = 384: up to this many windows, two workgroups share a window's heads
 void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
 {
     // every window gets a workgroup: with scores it finds its own rank (and may turn out pruned), otherwise
@@ -1371,12 +1375,8 @@ void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
 #undef WIN_CASE
 }
 
-#ifndef TOKEN_STREAM_SMALL
-#define TOKEN_STREAM_SMALL 128
-#endif
-#ifndef TOKEN_STREAM_FROM
-#define TOKEN_STREAM_FROM 12         // NH from which the streaming 64-row form is used (measured: the 32-row form wins below)
-#endif
+constexpr int TOKEN_STREAM_SMALL = 128;
+constexpr int TOKEN_STREAM_FROM = 12;        // NH from which the streaming 64-row form is used (measured: the 32-row form wins below)
 void launch_token(const Geom& G, const TokArgs& A, hipStream_t st)
 {
     if (G.rows_total == 0) return;

@@ -164,8 +164,12 @@ def make_feature_map(spec, seed, blobs=False, outlier_channels=False):
     return np.ascontiguousarray(x)
 
 
-def make_block_inputs(spec, seed, ranges=None, asymmetric=True):
-    """Weights, LayerNorm parameters, biases and quantizers of one block."""
+def make_block_inputs(spec, seed, ranges=None, asymmetric=True, per_branch_bias=False, bias_std=0.02):
+    """Weights, LayerNorm parameters, biases and quantizers of one block.
+
+    per_branch_bias=False: both branches carry the same bias arrays (the QAT setting, shadow layers
+    share weights and biases); True: the low branch gets biases of its own, drawn independently
+    (the PTQ setting, where the biases are made independent per branch)."""
     rng = _rng(seed, 10)
     C, F = spec.C, spec.C * spec.mlp_ratio
     ranges = dict(DEFAULT_RANGES, **(ranges or {}))
@@ -186,7 +190,9 @@ def make_block_inputs(spec, seed, ranges=None, asymmetric=True):
         b = (0.1 * rng.standard_normal(C)).astype(np.float32)
         return g, b
 
-    shared_bias = [(0.02 * rng.standard_normal(n)).astype(np.float32) for n in (3 * C, C, F, C)]
+    shared_bias = [(bias_std * rng.standard_normal(n)).astype(np.float32) for n in (3 * C, C, F, C)]
+    brng = _rng(seed, 11)                               # a stream of its own: the other draws do not move
+    own_bias = [(bias_std * brng.standard_normal(n)).astype(np.float32) for n in (3 * C, C, F, C)]
     branches = []
     for br, bits in enumerate((spec.act_bits_high, spec.act_bits_low)):
         g1, b1 = ln_pair()
@@ -198,8 +204,8 @@ def make_block_inputs(spec, seed, ranges=None, asymmetric=True):
             if name == "a_p":
                 sym = False
             q[name] = qparam_for_range(lo, hi, bits, symmetric=sym)
-        # shadow layers share weights and biases across the branches
-        branches.append(BranchParams(g1, b1, g2, b2, *shared_bias, q=q))
+        # shadow layers share weights and (unless per_branch_bias) biases across the branches
+        branches.append(BranchParams(g1, b1, g2, b2, *(own_bias if per_branch_bias and br == 1 else shared_bias), q=q))
     shared = SharedParams(w_qkv, w_proj, w_fc1, w_fc2, s_qkv, s_proj, s_fc1, s_fc2, rpb,
                           score_gamma=branches[0].ln1_gamma, score_beta=branches[0].ln1_beta)
     return BlockInputs(spec, shared, branches)
@@ -293,10 +299,6 @@ def backbone(name="cfg4"):
     for m, nxt in zip(merges, st[1:]):
         assert (m.Ho, m.Wo, m.N) == (nxt["spec"].H, nxt["spec"].W, nxt["spec"].C)
     return dict(wl, image=(s0.B, s0.H * 4, s0.W * 4), embed=embed, merges=merges)
-
-
-def keep_count(nW, keep_ratio):
-    return int(min(max(np.floor(keep_ratio * nW + 0.5), 0), nW))
 
 
 # The five benchmark workloads, as lists of stages; every stage is a run of

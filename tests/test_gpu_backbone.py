@@ -128,7 +128,7 @@ def test_config4_backbone_chain():
             y, tmp = torch.empty_like(cur), torch.empty_like(cur)
             scores = torch.empty((spec.B, spec.nW), dtype=torch.float64, device=dev)
             perm = torch.empty((spec.B, spec.nW), dtype=torch.int32, device=dev)
-            k = synth.keep_count(spec.nW, keep)
+            k = M.mixaq_keep_count(spec.nW, keep)
             n_pairs = (len(blocks) + 1) // 2
             M.mixaq_stage_forward([b[0] for b in blocks], cur, [k] * n_pairs, None, y, tmp, scores, perm, ws)
             torch.cuda.synchronize()
@@ -146,7 +146,7 @@ def test_config4_backbone_chain():
         assert np.array_equal(boundaries_gpu[bi], cur_o), "layer before stage %d" % si
         bi += 1
         spec = st["spec"]
-        k = synth.keep_count(spec.nW, keep)
+        k = O.keep_count(spec.nW, keep)
         perm_o = O.select_windows(O.score_windows(stage_inputs[si][0], cur_o), k)
         for inp, shift in zip(stage_inputs[si], st["shifts"]):
             cur_o, _ = O.block_forward(inp, cur_o, perm_o, k, shift, threads=16)

@@ -8,14 +8,16 @@ from paper_2507_19131_amd import synth
 pytestmark = pytest.mark.gpu
 
 gh = pytest.importorskip("gpu_harness") if torch.cuda.is_available() else None
+if torch.cuda.is_available():
+    from paper_2507_19131_amd import binding as M
 
-
-def _case(B, H, W, C, heads, shift, keep, seed, blobs=False, outliers=False, bits=(8, 4), wbits=8, ranges=None, mode=0):
+def _case(B, H, W, C, heads, shift, keep, seed, blobs=False, outliers=False, bits=(8, 4), wbits=8, ranges=None, mode=0,
+          mlp_ratio=4, **block_kw):
     spec = synth.BlockSpec(B, H, W, C, heads, shift=shift, act_bits_high=bits[0], act_bits_low=bits[1],
-                           weight_bits=wbits, score_mode=mode)
-    inp = synth.make_block_inputs(spec, seed, ranges=ranges)
+                           weight_bits=wbits, score_mode=mode, mlp_ratio=mlp_ratio)
+    inp = synth.make_block_inputs(spec, seed, ranges=ranges, **block_kw)
     x = synth.make_feature_map(spec, seed, blobs=blobs, outlier_channels=outliers)
-    return spec, inp, x, synth.keep_count(spec.nW, keep)
+    return spec, inp, x, M.mixaq_keep_count(spec.nW, keep)
 
 
 SMALL = [
@@ -53,6 +55,70 @@ def test_block_matches_oracle(B, H, W, C, heads, shift, keep, seed, kw, fused):
 
 @pytest.mark.parametrize("fused", [True, False])
 @pytest.mark.parametrize("shift", [0, 3])
+@pytest.mark.parametrize("C,heads,bits,wbits", [(96, 3, (8, 4), 8), (384, 12, (8, 4), 8), (768, 24, (4, 2), 4)])
+def test_independent_biases_per_branch(C, heads, bits, wbits, shift, fused):
+    """PTQ variant (Sec. 4.3, PTQ setup): the low branch has biases of its own, visibly different from the
+    high branch's; every tap must follow the bias of the row's branch."""
+    if fused and C > 384:
+        pytest.skip("the fused kernels cover C <= 384")
+    spec, inp, x, k = _case(2, 20, 27, C, heads, shift, 0.4, 51, blobs=True, bits=bits, wbits=wbits,
+                            per_branch_bias=True, bias_std=0.1)
+    for n in ("b_qkv", "b_proj", "b_fc1", "b_fc2"):
+        assert not np.array_equal(getattr(inp.branches[0], n), getattr(inp.branches[1], n))
+    print("independent biases", C, shift, "fused", fused, flush=True)
+    res = gh.compare_block(inp, x, k, fused=fused)
+    print(res, flush=True)
+    gh.assert_parity(res)
+
+
+@pytest.mark.parametrize("C,heads,mlp_ratio", [(96, 3, 3), (96, 3, 1), (192, 6, 3), (128, 4, 2), (96, 3, 8)])
+def test_other_mlp_ratios(C, heads, mlp_ratio):
+    """FFN widths other than 4C run the seven-kernel path; hidden sizes that are not a whole number of
+    ring turns of the long-K GEMM (9 or 3 slabs of 32) included."""
+    spec, inp, x, k = _case(2, 20, 27, C, heads, 3, 0.5, 52, blobs=True, mlp_ratio=mlp_ratio)
+    print("mlp_ratio", mlp_ratio, "C", C, flush=True)
+    res = gh.compare_block(inp, x, k)
+    print(res, flush=True)
+    gh.assert_parity(res)
+
+
+@pytest.mark.parametrize("fused", [True, False])
+@pytest.mark.parametrize("score_mode,value", [(0, float("nan")), (1, float("inf"))])
+def test_window_whose_score_is_not_a_number(score_mode, value, fused):
+    """A NaN in the map (or an Inf under the scoring LayerNorm) gives a NaN score: that window is ranked last,
+    the list stays a permutation, every kernel exits normally and all other windows match the oracle."""
+    import oracle_api as O
+    spec, inp, x, k = _case(2, 28, 35, 96, 3, 0, 0.5, 53, blobs=True, mode=score_mode)
+    x = x.copy()
+    x[1, 9, 16, 5] = value                                 # window (1, 2) of image 1
+    bad_w = 1 * 5 + 2
+    dev = torch.device("cuda:0")
+    xt = torch.from_numpy(x).to(dev)
+    print("NaN score case", score_mode, value, "fused", fused, flush=True)
+    with gh.GpuBlock(inp, fused=fused) as gb:
+        scores, perm = gb.score_select(xt, k)
+        y = gb.forward(xt, perm, k)
+        y2 = gb.forward(xt, None, k)                       # selection inside the call
+        torch.cuda.synchronize()
+    o_scores = O.score_windows(inp, x)
+    assert np.isnan(o_scores[1, bad_w]) and np.isnan(o_scores).sum() == 1
+    g_scores = scores.cpu().numpy()
+    assert np.array_equal(np.isnan(g_scores), np.isnan(o_scores))
+    o_perm = O.select_windows(o_scores, k)
+    assert np.array_equal(perm.cpu().numpy(), o_perm) and o_perm[1, -1] == bad_w
+    oy, _ = O.block_forward(inp, x, o_perm, k)
+    yn = y.cpu().numpy()
+    other = np.ones(yn.shape, dtype=bool)
+    other[1, 7:14, 14:21] = False
+    assert np.array_equal(yn[other], oy[other])
+    assert np.array_equal(np.isnan(yn), np.isnan(oy))
+    fin = ~np.isnan(oy)
+    assert np.array_equal(yn[fin], oy[fin])
+    assert np.array_equal(np.isnan(y2.cpu().numpy()), np.isnan(oy)) and torch.equal(torch.nan_to_num(y), torch.nan_to_num(y2))
+
+
+@pytest.mark.parametrize("fused", [True, False])
+@pytest.mark.parametrize("shift", [0, 3])
 def test_config2_full_size(shift, fused):
     """Swin-T stage 1 at detection scale, the size the benchmark times."""
     spec, inp, x, k = _case(1, 200, 336, 96, 3, shift, 0.5, 1002, blobs=True)
@@ -64,7 +130,6 @@ def test_config2_full_size(shift, fused):
 
 def test_maximum_window_count():
     """4096 windows per image is the most the selection handles (448x448 map, shifted); more is refused."""
-    from paper_2507_19131_amd import binding as M
     spec, inp, x, k = _case(1, 448, 448, 96, 3, 3, 0.5, 23, blobs=True)
     assert spec.nW == 4096
     print("maximum window count", flush=True)
@@ -98,7 +163,6 @@ def test_order_invariance_and_reverse_selection():
 
 
 def test_error_paths_do_not_launch():
-    from paper_2507_19131_amd import binding as M
     spec, inp, x, k = _case(1, 14, 14, 96, 3, 0, 0.5, 22)
     sh, br = M.to_device(inp)
     d = M.make_desc(spec)
@@ -135,7 +199,6 @@ def test_error_paths_do_not_launch():
 def test_activation_pruning_matches_oracle(shift, kh_frac, kl_frac, fused):
     """Three-way split (Sec. 3.4): high, low, pruned windows; pruned features are forwarded."""
     import oracle_api as O
-    from paper_2507_19131_amd import binding as M
     spec, inp, x, _ = _case(2, 26, 33, 96, 3, shift, 0.5, 31, blobs=True)
     nW = spec.nW
     kh, kl = int(kh_frac * nW), int(kl_frac * nW)
@@ -165,7 +228,6 @@ def test_forward_from_scores_matches_oracle(C, heads, shift, kh_frac, kl_frac):
     """The selection taken inside the first kernel from the stage's scores (fused path) or by the
     select kernel (seven-kernel path, C = 768) gives the oracle's block output."""
     import oracle_api as O
-    from paper_2507_19131_amd import binding as M
     spec, inp, x, _ = _case(2, 26, 33, C, heads, shift, 0.5, 41, blobs=True)
     nW = spec.nW
     kh = int(kh_frac * nW)

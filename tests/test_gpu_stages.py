@@ -19,7 +19,7 @@ def run_stage(spec, shifts, keep, seed, blobs, outliers, ranges):
     dev = torch.device("cuda:0")
     x_np = synth.make_feature_map(spec, seed, blobs=blobs, outlier_channels=outliers)
     inputs = [synth.make_block_inputs(spec, seed + 10 * i, ranges=ranges) for i in range(len(shifts))]
-    k = synth.keep_count(spec.nW, keep)
+    k = M.mixaq_keep_count(spec.nW, keep)
     x = torch.from_numpy(x_np).to(dev)
     blocks = [gh.GpuBlock(inp, shift) for inp, shift in zip(inputs, shifts)]
     try:
@@ -127,7 +127,7 @@ def test_stage_on_a_side_stream_matches_the_default_stream():
     x = torch.from_numpy(synth.make_feature_map(spec, 88, blobs=True)).to(dev)
     blocks = [gh.GpuBlock(synth.make_block_inputs(spec, 880 + i), shift) for i, shift in enumerate(st["shifts"])]
     try:
-        k = synth.keep_count(spec.nW, 0.5)
+        k = M.mixaq_keep_count(spec.nW, 0.5)
         outs = []
         side = torch.cuda.Stream()
         for stream in (None, side):
@@ -160,7 +160,7 @@ def test_config2_stage_call_as_the_benchmark_launches_it():
     spec = st["spec"]
     x_np = synth.make_feature_map(spec, wl["seed"], blobs=wl["blobs"], outlier_channels=wl["outliers"])
     inputs = [synth.make_block_inputs(spec, wl["seed"] + 10 * i) for i, _ in enumerate(st["shifts"])]
-    k = synth.keep_count(spec.nW, wl["keep"][0])
+    k = M.mixaq_keep_count(spec.nW, wl["keep"][0])
     dev = torch.device("cuda:0")
     x = torch.from_numpy(x_np).to(dev)
     blocks = [gh.GpuBlock(inp, shift) for inp, shift in zip(inputs, st["shifts"])]
@@ -191,7 +191,7 @@ def test_stage_call_can_be_captured_in_a_graph():
     xs = [torch.from_numpy(synth.make_feature_map(spec, 90 + i, blobs=True)).to(dev) for i in range(3)]
     blocks = [gh.GpuBlock(synth.make_block_inputs(spec, 900 + i), shift) for i, shift in enumerate([0, 3])]
     try:
-        k = synth.keep_count(spec.nW, 0.5)
+        k = M.mixaq_keep_count(spec.nW, 0.5)
         x = xs[0].clone()
         y, tmp = torch.empty_like(x), torch.empty_like(x)
         scores = torch.empty((spec.B, spec.nW), dtype=torch.float64, device=dev)

@@ -105,7 +105,12 @@ def test_keep_count_values():
     # 0.4*1369 = 547.6 -> 548, 0.4*361 = 144.4 -> 144 (round half up of keep*nW)
     for nW, keep, k in ((1369, 0.4, 548), (361, 0.4, 144), (1392, 0.5, 696), (96, 0.25, 24), (96, 0.75, 72),
                         (64, 0.5, 32), (5, 0.5, 3), (10, 0.0, 0), (10, 1.0, 10)):
-        assert O.keep_count(nW, keep) == k == synth.keep_count(nW, keep)
+        assert O.keep_count(nW, keep) == k
+    # round half up, per image, clamped: exact rational arithmetic on a sweep (ties at keep*nW = n + 1/2 included)
+    for nW in (1, 2, 3, 5, 24, 49, 96, 361, 1369, 1392, 4096):
+        for num in range(0, 21):
+            want = (Fraction(num, 20) * nW + Fraction(1, 2)).__floor__()
+            assert O.keep_count(nW, num / 20) == min(max(want, 0), nW), (nW, num)
 
 
 # ---------------------------------------------------------------- geometry
@@ -208,9 +213,9 @@ def test_selection_against_sort():
 
 
 # ---------------------------------------------------------------- whole block
-def _setup(H, W, Cc, heads, shift, seed, Bn=1, blobs=True, bits=(8, 4), wbits=8):
+def _setup(H, W, Cc, heads, shift, seed, Bn=1, blobs=True, bits=(8, 4), wbits=8, **block_kw):
     spec = synth.BlockSpec(Bn, H, W, Cc, heads, shift=shift, act_bits_high=bits[0], act_bits_low=bits[1], weight_bits=wbits)
-    return spec, synth.make_block_inputs(spec, seed), synth.make_feature_map(spec, seed, blobs=blobs)
+    return spec, synth.make_block_inputs(spec, seed, **block_kw), synth.make_feature_map(spec, seed, blobs=blobs)
 
 
 @pytest.mark.parametrize("H,W,shift", [(28, 35, 0), (26, 33, 3), (14, 14, 3)])
@@ -262,6 +267,73 @@ def test_close_to_float_swin_block(H, W, Cc, heads, shift):
     assert sq[0] > sq[1] > sq[2] >= 5.0, sq
 
 
+def test_per_branch_biases_follow_the_windows_branch():
+    """PTQ variant (Sec. 4.3, PTQ setup): biases independent per branch.  With large, distinct biases the
+    block tracks the float block that gives every window the biases of ITS branch, and is far from the
+    float blocks a bias mix-up would produce (both branches reading the high set, the low set, or swapped)."""
+    wide = {"a_q": (-4.0, 4.0), "a_k": (-4.0, 4.0), "a_v": (-4.0, 4.0), "a_proj_in": (-3.0, 3.0), "a_fc2_in": (-0.17, 4.0)}
+    spec, inp, x = _setup(21, 28, 64, 2, 3, 27, bits=(8, 8), per_branch_bias=True, bias_std=0.5, ranges=wide)
+    nW = spec.nW
+    k = nW // 2
+    perm = O.select_windows(O.score_windows(inp, x), k)
+    y, _ = O.block_forward(inp, x, perm, k)
+    brw = np.ones((1, nW), dtype=int)
+    brw[0, perm[0, :k]] = 0
+    good = sqnr_db(float_block(inp, x, brw) - x, y - x)
+    import copy
+    names = ("b_qkv", "b_proj", "b_fc1", "b_fc2")
+    bad = []
+    for mix in ("both_high", "both_low", "swapped"):
+        wrong = copy.deepcopy(inp)
+        for n in names:
+            hi, lo = getattr(inp.branches[0], n), getattr(inp.branches[1], n)
+            setattr(wrong.branches[0], n, lo if mix != "both_high" else hi)
+            setattr(wrong.branches[1], n, hi if mix != "both_low" else lo)
+        bad.append(sqnr_db(float_block(wrong, x, brw) - x, y - x))
+    assert good >= 40.0, (good, bad)
+    assert max(bad) <= 10.0, (good, bad)
+    # one layer at a time: moving a single bias of the low branch to the high branch's values is seen
+    for n in names:
+        wrong = copy.deepcopy(inp)
+        setattr(wrong.branches[1], n, getattr(inp.branches[0], n))
+        assert sqnr_db(float_block(wrong, x, brw) - x, y - x) <= 25.0, n
+
+
+def test_selection_with_scores_that_are_not_numbers():
+    """A NaN score is ranked as the least important value in both directions; the list stays a permutation
+    and the other windows keep their order."""
+    rng = np.random.default_rng(12)
+    sc = rng.standard_normal((2, 23))
+    sc[0, [4, 17]] = np.nan
+    sc[1, 0] = np.nan
+    sc[1, 5] = np.inf
+    for reverse in (0, 1):
+        perm = O.select_windows(sc, 7, reverse)
+        for b in range(2):
+            assert np.array_equal(np.sort(perm[b]), np.arange(23))
+            nan_idx = np.flatnonzero(np.isnan(sc[b]))
+            assert np.array_equal(perm[b, 23 - len(nan_idx):], nan_idx)            # last, by index
+            rest = perm[b, :23 - len(nan_idx)]
+            key = sc[b][rest] if reverse else -sc[b][rest]
+            assert np.all(np.diff(key) >= 0)
+    # a NaN in the map: the quantizers saturate on it, so it survives only along the residual path, in place
+    spec, inp, x = _setup(21, 21, 32, 1, 0, 28)
+    x = x.copy()
+    x[0, 8, 9, 3] = np.nan                                  # inside window 4 of the 3x3 grid
+    s = O.score_windows(inp, x)
+    assert np.isnan(s[0, 4]) and np.isnan(s).sum() == 1
+    perm = O.select_windows(s, 4)
+    assert perm[0, -1] == 4
+    y, _ = O.block_forward(inp, x, perm, 4)
+    assert np.array_equal(np.argwhere(np.isnan(y)), [[0, 8, 9, 3]])
+    clean = x.copy()
+    clean[0, 8, 9, 3] = 0.0
+    yc, _ = O.block_forward(inp, clean, perm, 4)
+    other = np.ones(y.shape, dtype=bool)
+    other[0, 7:14, 7:14] = False                            # the other windows do not see it
+    assert np.array_equal(y[other], yc[other])
+
+
 def _rn32(fr):
     """Round a Fraction to the nearest binary32 (ties to even)."""
     f = np.float32(float(fr))                      # double rounding is repaired below
@@ -270,10 +342,15 @@ def _rn32(fr):
     return np.float32(best)
 
 
-def test_taps_stage_by_stage():
+@pytest.mark.parametrize("per_branch_bias", [False, True])
+def test_taps_stage_by_stage(per_branch_bias):
     """Every integer stage recomputed from the previous tap with int64 numpy;
-    float->code stages re-evaluated exactly (rational arithmetic) on samples."""
-    spec, inp, x = _setup(19, 24, 64, 2, 3, 23, Bn=2)
+    float->code stages re-evaluated exactly (rational arithmetic) on samples.  With per_branch_bias the
+    low branch has biases of its own (Sec. 4.3, PTQ setup): each sample takes the bias of ITS branch."""
+    spec, inp, x = _setup(19, 24, 64, 2, 3, 23, Bn=2, per_branch_bias=per_branch_bias, bias_std=0.05)
+    if per_branch_bias:
+        for n in ("b_qkv", "b_proj", "b_fc1", "b_fc2"):
+            assert not np.array_equal(getattr(inp.branches[0], n), getattr(inp.branches[1], n))
     nW, k = spec.nW, 5
     perm = O.select_windows(O.score_windows(inp, x), k)
     y, t = O.block_forward(inp, x, perm, k, want_taps="all")
@@ -304,6 +381,7 @@ def test_taps_stage_by_stage():
     assert np.array_equal(O.scatter_windows(spec, t["y_win"], perm), y)
     rng = np.random.default_rng(1)
     f32 = lambda v: Fraction(float(np.float32(v)))
+    shortcut, _ = O.gather_windows(spec, x, perm)          # the gather is pinned to numpy pad/roll/reshape above
     for _ in range(400):
         g, tok = rng.integers(S), rng.integers(49)
         b = inp.branches[br_of_slot[g]]
@@ -318,6 +396,9 @@ def test_taps_stage_by_stage():
         n = rng.integers(Cc)
         f = _rn32(Fraction(int(t["acc_o"][g, tok, n])) * f32(np.float32(b.q["a_p"][0]) * np.float32(b.q["a_v"][0])))
         assert t["a_proj_in"][g, tok, n] == _q_exact(f, *b.q["a_proj_in"], bits)
+        # projection epilogue + first residual: h = rn32(rn32(acc*m + bias) + shortcut), shortcut 0 on padding
+        f = _rn32(Fraction(int(t["acc_proj"][g, tok, n])) * f32(np.float32(b.q["a_proj_in"][0]) * sh.s_proj[n]) + f32(b.b_proj[n]))
+        assert t["h"][g, tok, n] == _rn32(f32(f) + f32(shortcut[g, tok, n]))
         # fc2 epilogue + residual
         f = _rn32(Fraction(int(t["acc_fc2"][g, tok, n])) * f32(np.float32(b.q["a_fc2_in"][0]) * sh.s_fc2[n]) + f32(b.b_fc2[n]))
         assert t["y_win"][g, tok, n] == np.float32(f + t["h"][g, tok, n])
