@@ -193,6 +193,22 @@ int mixaq_block_forward_taps(const mixaq_block *blk, const float *x, const int32
                              float *y, void *workspace, size_t workspace_bytes, void *stream,
                              const mixaq_taps *taps);
 
+/* For callers that cannot allocate device memory or bring a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same computation and same bits as
+ * mixaq_block_forward, with the scratch the two fused kernels exchange (scores, selection list, row
+ * bookkeeping, attention-output codes) held in a static device array of MIXAQ_STATIC_SCRATCH_BYTES
+ * inside the library: one copy per GPU, kept until the process ends.  The call allocates nothing and
+ * frees nothing; on its first use on a device it asks the runtime for the array's address there
+ * (the device must be current, as for every call).  Only blocks that run the fused kernels
+ * (C <= 384, mlp_ratio 4, not switched off by mixaq_block_set_fused: MIXAQ_E_SHAPE otherwise) and
+ * whose scratch fits: about B*nW*49*(C + 8) bytes, e.g. 7.1 MB for the 1392-window stage-1 map at
+ * C = 96; MIXAQ_E_WORKSPACE with the two sizes in the message otherwise.  Every call on a GPU uses
+ * that GPU's one array, which keeps the last call's contents (nothing in it needs clearing: every
+ * call rewrites what it reads): calls that overlap in time on one GPU, on any streams, race. */
+#define MIXAQ_STATIC_SCRATCH_BYTES (16u << 20)
+int mixaq_block_forward_static(const mixaq_block *blk, const float *x, const int32_t *perm, int32_t k_high,
+                               float *y, void *stream);
+
 /* ---- layers between stages ---------------------------------------------------------------- */
 
 /* Patch embedding and patch merging of the Swin backbone the blocks sit in.  The paper keeps them

@@ -81,6 +81,7 @@ def load():
         L.mixaq_block_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                           C.c_size_t, C.c_void_p]
         L.mixaq_block_forward_taps.argtypes = L.mixaq_block_forward.argtypes + [C.c_void_p]
+        L.mixaq_block_forward_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.mixaq_select_windows3.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                             C.c_void_p]
         L.mixaq_block_forward_pruned.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
@@ -190,6 +191,12 @@ def mixaq_block_forward_pruned(blk, x, perm, k_high, k_low, y, workspace, stream
 def mixaq_block_forward(blk, x, perm, k_high, y, workspace, stream=None):
     _check(load().mixaq_block_forward(blk, _ptr(x), _ptr(perm), k_high, _ptr(y), _ptr(workspace),
                                       workspace.numel() * workspace.element_size(), _stream(stream)))
+    return y
+
+
+def mixaq_block_forward_static(blk, x, perm, k_high, y, stream=None):
+    """The block on the library's static scratch: no workspace argument, nothing allocated."""
+    _check(load().mixaq_block_forward_static(blk, _ptr(x), _ptr(perm), k_high, _ptr(y), _stream(stream)))
     return y
 
 

@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -144,12 +145,39 @@ struct mixaq_block {
     float* tok_params[2] = {nullptr, nullptr};   // parameter blocks of the fused token kernel
     const float4* gelu_tab = nullptr;            // cubic coefficients of the pinned GELU
     size_t ws_bytes = 0;
+    size_t ws_fused_bytes = 0; // what the two fused kernels alone need
     int rows_max = 0;
     bool fused_window = false; // the window kernel instead of gather/LN1 + QKV + attention kernels
     bool fused_token = false;  // the token kernel instead of proj + LN2 + FC1 + FC2 kernels
 };
 
+// ---- scratch of the entry point that allocates nothing -------------------------------------------
+// One array per GPU the library runs on, held until the process ends.  Host code never uses the
+// array's name as an address: static_scratch() asks the runtime for the device address once per
+// device and every later use goes through that pointer.
+static __device__ __align__(256) unsigned char scratch[MIXAQ_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+
+int static_scratch(void** out)
+{
+    static std::mutex mu;
+    static void* ptr[MAX_DEVICES] = {};
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(MIXAQ_E_HIP, "device %d outside 0..%d", dev, MAX_DEVICES - 1);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(MIXAQ_E_HIP, "the runtime returned no address for the static scratch");
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return MIXAQ_OK;
+}
 
 // packs W[N,K] (row-major int8) into MFMA A-operand order and builds the per-branch epilogue constants
 int prepare_linear(mixaq_block* blk, Linear& L, const int8_t* w_dev, const float* s_dev, int N, int K,
@@ -242,18 +270,22 @@ struct Workspace {
     int8_t *a1, *qkv, *ao, *a2, *g; float* h;
 };
 
-size_t carve(const mixaq_block* b, char* base, Workspace* w)
+// fused_only: only what the window kernel and the token kernel exchange (scores, list, row bookkeeping,
+// attention-output codes); the buffers of the seven-kernel path stay NULL
+size_t carve(const mixaq_block* b, char* base, Workspace* w, bool fused_only = false)
 {
     size_t off = 0;
     const size_t R = b->rows_max, C = b->d.C, S = (size_t)b->d.B * b->nW, F = C * b->d.mlp_ratio;
     auto take = [&](size_t bytes) { char* p = base ? base + off : nullptr; off += align256(bytes); return p; };
+    *w = Workspace{};
     w->scores = (double*)take(S * 8);
     w->perm = (int*)take(S * 4);
     w->row_pix = (int*)take(R * 4);
     w->row_canon = (int*)take(R * 4);
+    w->ao = (int8_t*)take(R * C);
+    if (fused_only) return off;
     w->a1 = (int8_t*)take(R * C);
     w->qkv = (int8_t*)take(R * 3 * C);
-    w->ao = (int8_t*)take(R * C);
     w->h = (float*)take(R * C * 4);
     w->a2 = (int8_t*)take(R * C);
     w->g = (int8_t*)take(R * F);
@@ -270,7 +302,7 @@ struct Prof {
 
 int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, const double* scores, int32_t k_high,
                  int32_t k_low, float* y, void* workspace, size_t workspace_bytes, void* stream, const mixaq_taps* taps,
-                 Prof* prof = nullptr, int32_t* perm_out = nullptr)
+                 Prof* prof = nullptr, int32_t* perm_out = nullptr, bool fused_only = false)
 {
     if (!blk) return fail(MIXAQ_E_NULL, "block is NULL");
     if (!x || !y) return fail(MIXAQ_E_NULL, "x or y is NULL");
@@ -278,7 +310,10 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, co
     if (k_low < 0) k_low = blk->nW - k_high;      // no pruning
     if (k_high < 0 || k_low < 0 || k_high + k_low > blk->nW)
         return fail(MIXAQ_E_SHAPE, "k_high=%d, k_low=%d do not fit %d windows", k_high, k_low, blk->nW);
-    if (workspace_bytes < blk->ws_bytes) return fail(MIXAQ_E_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, blk->ws_bytes);
+    if (fused_only && !(blk->fused_window && blk->fused_token))
+        return fail(MIXAQ_E_SHAPE, "this call needs the fused kernels (C <= 384, mlp_ratio 4, not switched off)");
+    const size_t ws_need = fused_only ? blk->ws_fused_bytes : blk->ws_bytes;
+    if (workspace_bytes < ws_need) return fail(MIXAQ_E_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, ws_need);
     if ((uintptr_t)workspace & 255) return fail(MIXAQ_E_WORKSPACE, "workspace must be 256-byte aligned");
     {
         const char *xa = (const char*)x, *ya = (const char*)y;
@@ -290,7 +325,7 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, co
     Geom G;
     make_geom(blk, k_high, k_low, &G);
     Workspace ws;
-    carve(blk, (char*)workspace, &ws);
+    carve(blk, (char*)workspace, &ws, fused_only);
     static const mixaq_taps no_taps = {};
     const mixaq_taps& tp = taps ? *taps : no_taps;
 
@@ -548,6 +583,7 @@ int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* 
     b->rows_max = round_up(desc->B * b->nW * TOK, ROW_TILE) + ROW_TILE;
     Workspace w;
     b->ws_bytes = carve(b, nullptr, &w);
+    b->ws_fused_bytes = carve(b, nullptr, &w, true);
     *out = b;
     return MIXAQ_OK;
 }
@@ -653,6 +689,22 @@ int mixaq_block_forward_taps(const mixaq_block* blk, const float* x, const int32
                              void* workspace, size_t workspace_bytes, void* stream, const mixaq_taps* taps)
 {
     return forward_impl(blk, x, perm, nullptr, k_high, -1, y, workspace, workspace_bytes, stream, taps);
+}
+
+int mixaq_block_forward_static(const mixaq_block* blk, const float* x, const int32_t* perm, int32_t k_high, float* y,
+                               void* stream)
+{
+    if (!blk) return fail(MIXAQ_E_NULL, "block is NULL");
+    if (!(blk->fused_window && blk->fused_token))
+        return fail(MIXAQ_E_SHAPE, "this call needs the fused kernels (C <= 384, mlp_ratio 4, not switched off)");
+    if (blk->ws_fused_bytes > (size_t)MIXAQ_STATIC_SCRATCH_BYTES)
+        return fail(MIXAQ_E_WORKSPACE, "the map needs %zu bytes of scratch, the static scratch holds %zu", blk->ws_fused_bytes,
+                    (size_t)MIXAQ_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    int rc = static_scratch(&ws);
+    if (rc) return rc;
+    return forward_impl(blk, x, perm, nullptr, k_high, -1, y, ws, (size_t)MIXAQ_STATIC_SCRATCH_BYTES, stream, nullptr, nullptr, nullptr,
+                        true);
 }
 
 int mixaq_block_set_fused(mixaq_block* blk, int32_t enable)
