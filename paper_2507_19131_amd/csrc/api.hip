@@ -8,6 +8,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "../../include/mixaq.h"
@@ -143,6 +144,7 @@ struct mixaq_block {
     QDev q_in[2], q_qkv[2][3], q_p[2], q_ao[2], q_fc1in[2], q_fc2in[2];
     float m2[2], m_o[2];
     float* tok_params[2] = {nullptr, nullptr};   // parameter blocks of the fused token kernel
+    float* win_params[2] = {nullptr, nullptr};   // parameter blocks of the fused window kernel
     const float4* gelu_tab = nullptr;            // cubic coefficients of the pinned GELU
     size_t ws_bytes = 0;
     size_t ws_fused_bytes = 0; // what the two fused kernels alone need
@@ -362,8 +364,7 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, co
         wa.y = y; wa.eps = d.ln_eps; wa.Wqkv = blk->qkv.Wp; wa.bias2 = blk->bias2; wa.out = ws.ao;
         wa.row_pix = ws.row_pix; wa.row_canon = ws.row_canon;
         for (int br = 0; br < 2; ++br) {
-            wa.gamma[br] = blk->ln_gamma[0][br]; wa.beta[br] = blk->ln_beta[0][br]; wa.q_in[br] = blk->q_in[br];
-            wa.m[br] = blk->qkv.m[br]; wa.bias[br] = blk->qkv.bias[br]; wa.negcorr[br] = blk->qkv.negcorr[br];
+            wa.params[br] = blk->win_params[br]; wa.q_in[br] = blk->q_in[br];
             for (int k = 0; k < 3; ++k) wa.q_qkv[br][k] = blk->q_qkv[br][k];
             wa.m2[br] = blk->m2[br]; wa.m_o[br] = blk->m_o[br]; wa.qp[br] = blk->q_p[br]; wa.qo[br] = blk->q_ao[br];
         }
@@ -564,6 +565,23 @@ int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* 
     }
     b->fused_window = fused_window_supported(C);
     b->fused_token = fused_token_supported(C, desc->mlp_ratio);
+    auto gather_block = [&](const std::vector<std::pair<const void*, int>>& parts, float** dst) {
+        size_t words = 0;
+        for (auto& pt : parts) words += pt.second;
+        std::vector<float> blkp(words);
+        size_t off = 0;
+        for (auto& pt : parts) {
+            if (hipMemcpy(blkp.data() + off, pt.first, (size_t)pt.second * 4, hipMemcpyDeviceToHost) != hipSuccess)
+                return fail(MIXAQ_E_HIP, "copy of a parameter block failed");
+            off += pt.second;
+        }
+        return upload(b->owned, blkp, dst);
+    };
+    if (b->fused_window)      // parameter blocks of the window kernel
+        for (int br = 0; br < 2; ++br)
+            if ((rc = gather_block({{b->ln_gamma[0][br], C}, {b->ln_beta[0][br], C}, {b->qkv.m[br], 3 * C}, {b->qkv.bias[br], 3 * C},
+                                    {b->qkv.negcorr[br], 3 * C}}, &b->win_params[br])))
+                return bail(rc);
     if (b->fused_token) {     // parameter blocks of the token kernel: device-to-device gathers of what was just uploaded
         for (int br = 0; br < 2; ++br) {
             std::vector<float> blkp((size_t)8 * C + 3 * F);

@@ -72,14 +72,12 @@ struct WinArgs {                     // fused window kernel (gather + LN1 + QKV 
     int reverse;                     // with scores: invert the order of importance
     int* perm_out;                   // with scores: receives the selection list
     float* y;                        // with scores: pruned windows are forwarded here
-    const float* gamma[2];
-    const float* beta[2];
+    // per branch one block of 32-bit words, staged in LDS by every workgroup:
+    // [LN1 gamma | LN1 beta] (C words each), then [qkv m | qkv bias | qkv negcorr] (3C words each; negcorr integers)
+    const float* params[2];
     float eps;
     QDev q_in[2];
     const v4i* Wqkv;                 // packed, natural k order
-    const float* m[2];
-    const float* bias[2];
-    const int* negcorr[2];
     QDev q_qkv[2][3];
     const float* bias2;
     float m2[2], m_o[2];

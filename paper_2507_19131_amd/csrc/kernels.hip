@@ -571,18 +571,29 @@ struct WinCfg {
     static constexpr int NV = NH * HG * 32 / (4 * LPT);              // float4 per lane = 8 * HG
 };
 
+// word offsets inside the window kernel's parameter block of one branch (see WinArgs::params)
+template <int C> struct WinPrm {
+    static constexpr int LN_G = 0, LN_B = C, M = 2 * C, B = 5 * C, NC = 8 * C, WORDS = 11 * C;
+};
+
 template <int NH, bool TAPS, bool SCORED, int HG = 1>
 __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 2 && NH <= 8) ? 2 : WIN_WAVES_PER_EU))) void window_kernel(Geom G, WinArgs A)
 {
     constexpr int NHT = NH * HG;                                         // heads of the block; this workgroup runs NH of them
     constexpr int C = NHT * 32, KS = NHT, LPT = WinCfg<NH, HG>::LPT, NV = WinCfg<NH, HG>::NV, NT = NH * 64;
     constexpr int GPW = WinCfg<NH, HG>::GPW;
+    using PR = WinPrm<C>;
     const int widx = HG == 1 ? blockIdx.x : blockIdx.x / HG, hg = HG == 1 ? 0 : blockIdx.x % HG;
     static_assert(NH * GPW >= TOK, "one pass must cover the window");
     __shared__ v4i a1s[2 * KS * 64];                                     // LN1 codes as fragments [token block][k slab][lane]
+    __shared__ __attribute__((aligned(16))) float prm[PR::WORDS];        // this branch's LN1 affine and QKV epilogue constants
     __shared__ __attribute__((aligned(16))) int csum[NH][HD];
     __shared__ int red[NH];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, g = lane >> 5;
+    const int head = hg * NH + wave;
+    constexpr bool HOIST = KS <= 8;
+    constexpr int RING = 6;
+    auto weights_of = [&](int which) { return A.Wqkv + (size_t)(which * NHT + head) * KS * 64 + lane; };
     // SCORED: the workgroup is given a window and finds its own place in the selection (its rank
     // under the total order of the scores); otherwise it is given a slot and looks the window up.
     int branch = 0, row0 = 0, canon_slot = 0, w, bimg;
@@ -655,7 +666,7 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
         int rank = 0;
 #pragma unroll
         for (int k = 0; k < NH; ++k) rank += red[k];
-        if (tid == 0) A.perm_out[(size_t)bimg * G.nW + rank] = w;
+        if (tid == 0 && hg == 0) A.perm_out[(size_t)bimg * G.nW + rank] = w;
         if (rank >= G.k_hi + G.k_lo) {                                    // pruned (Sec. 3.4): forward the features
             if (pix >= 0 && hg == 0) {
                 float* dst = A.y + (size_t)pix * C;
@@ -668,11 +679,22 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
         if (rank < G.k_hi) { branch = 0; row0 = (bimg * G.k_hi + rank) * TOK; }
         else { branch = 1; row0 = G.base_lo + (bimg * G.k_lo + rank - G.k_hi) * TOK; }
     }
+    {   // the branch is known: its parameter block goes to LDS (requested now, so that it travels with the map)
+        const float4* src = (const float4*)A.params[branch];
+        constexpr int PV = PR::WORDS / 4, PVT = (PV + NT - 1) / NT;
+        float4 pv[PVT];
+#pragma unroll
+        for (int k = 0; k < PVT; ++k) pv[k] = src[min(tid + k * NT, PV - 1)];
+#pragma unroll
+        for (int k = 0; k < PVT; ++k) if (tid + k * NT < PV) ((float4*)prm)[tid + k * NT] = pv[k];
+    }
+    __syncthreads();                                                     // parameter block visible
+    const int* prmi = (const int*)prm;
     if (t < TOK) {
         const int canon = canon_slot * TOK + t;
-        if (sub == 0) { A.row_pix[row0 + t] = pix; A.row_canon[row0 + t] = canon; }
+        if (sub == 0 && hg == 0) { A.row_pix[row0 + t] = pix; A.row_canon[row0 + t] = canon; }
         if (pix >= 0) {
-            token_layernorm<LPT, NV>(v, C, A.eps, A.gamma[branch], A.beta[branch], sub, first);
+            token_layernorm<LPT, NV>(v, C, A.eps, prm + PR::LN_G, prm + PR::LN_B, sub, first);
         } else {
 #pragma unroll
             for (int k = 0; k < NV; ++k) v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -683,16 +705,13 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
             const int ch = (k * LPT + sub) * 4;
             int code = pack4(quant_code(v[k].x, q), quant_code(v[k].y, q), quant_code(v[k].z, q), quant_code(v[k].w, q));
             a1w[frag_dw(t, ch)] = code;
-            if (TAPS && A.tap_a1) *(int*)(A.tap_a1 + (size_t)canon * C + ch) = code;
+            if (TAPS && A.tap_a1 && hg == 0) *(int*)(A.tap_a1 + (size_t)canon * C + ch) = code;
         }
     }
     __syncthreads();
-    const int head = hg * NH + wave;
     // Operand handling.  Up to eight heads the LN1 fragments of both token blocks and the weight
     // fragments of one output block sit in registers; beyond that the B operand is read from LDS
     // inside the chain and the weight fragments stream through a short ring.
-    constexpr bool HOIST = KS <= 8;
-    constexpr int RING = 6;
     v4i bf[2][HOIST ? KS : 1];
     if (HOIST) {
 #pragma unroll
@@ -720,12 +739,11 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
     for (int which = 0; which < 2; ++which) {
         const int nb = which * NHT + head;
         const QDev qq = A.q_qkv[branch][which];
-        const v4i* wp = A.Wqkv + (size_t)nb * KS * 64 + lane;
+        const v4i* wp = weights_of(which);
         auto start = [&](v16i& acc) {                                     // accumulators start at -zp * colsum
-            const int* nc = A.negcorr[branch] + nb * 32 + g * 4;
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
-                int4 t4 = *(const int4*)(nc + qd * 8);
+                const int4 t4 = *(const int4*)(prmi + PR::NC + nb * 32 + qd * 8 + g * 4);
                 acc[qd * 4 + 0] = t4.x; acc[qd * 4 + 1] = t4.y; acc[qd * 4 + 2] = t4.z; acc[qd * 4 + 3] = t4.w;
             }
         };
@@ -735,7 +753,7 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 const int n0 = nb * 32 + qd * 8 + g * 4;
-                const float4 m = *(const float4*)(A.m[branch] + n0), bs = *(const float4*)(A.bias[branch] + n0);
+                const float4 m = *(const float4*)(prm + PR::M + n0), bs = *(const float4*)(prm + PR::B + n0);
                 const int a0 = acc[qd * 4 + 0], a1 = acc[qd * 4 + 1], a2 = acc[qd * 4 + 2], a3 = acc[qd * 4 + 3];
                 wd[qd] = pack4(quant_code(fmaf((float)a0, m.x, bs.x), qq), quant_code(fmaf((float)a1, m.y, bs.y), qq),
                                quant_code(fmaf((float)a2, m.z, bs.z), qq), quant_code(fmaf((float)a3, m.w, bs.w), qq));
@@ -770,9 +788,9 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
     v4i vt[2];
     {
         const int nb = 2 * NHT + head, n = nb * 32 + j;                   // this lane's output channel (dim j of the head)
-        const v4i* wp = A.Wqkv + (size_t)nb * KS * 64 + lane;
-        const float m = A.m[branch][n], bs = A.bias[branch][n];
-        const int nc = A.negcorr[branch][n];
+        const v4i* wp = weights_of(2);
+        const float m = prm[PR::M + n], bs = prm[PR::B + n];
+        const int nc = prmi[PR::NC + n];
         const QDev qv = A.q_qkv[branch][2];
         int cs = 0;
         auto finish = [&](int tb, const v16i& acc) {
@@ -1077,12 +1095,6 @@ __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A
         actf[((r >> 5) * KS + (q >> 1)) * 64 + (q & 1) * 32 + (r & 31)] = *(const v4i*)(A.ao + (size_t)(row_base + r) * C + q * 16);
     }
     gelu_stage_table(gtab, A.gelu_tab, tid, NT);
-    float4 sc[RB][4];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd)
-            sc[rb][qd] = pix[rb] >= 0 ? *(const float4*)(A.x + (size_t)pix[rb] * C + nb * 32 + qd * 8 + g * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
     // acc[rb] += W(fragments wp[0], wp[64], ...) * operand fragments b[(rb * stride_rb + i) * 64 + lane]
     auto start = [&](v16i* acc, int off) {                             // accumulators start at -zp * colsum
 #pragma unroll
@@ -1117,6 +1129,12 @@ __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A
     {   // output projection + first residual
         const v4i* wp = A.Wproj + (size_t)nb * KS * 64 + lane;
         request(wp);
+        float4 sc[RB][4];                                              // shortcut of the first residual, in flight during the chain
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd)
+                sc[rb][qd] = pix[rb] >= 0 ? *(const float4*)(A.x + (size_t)pix[rb] * C + nb * 32 + qd * 8 + g * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
         v16i acc[RB];
         start(acc, PR::P_NC + nb * 32);
         chain(wp, actf, KS, 1, KS, acc);
@@ -1235,6 +1253,227 @@ __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A
             const float4 m = *(const float4*)(prm + PR::F2_M + n0), bs = *(const float4*)(prm + PR::F2_B + n0);
             float4 o4 = make_float4(fmaf((float)acc2[rb][qd * 4 + 0], m.x, bs.x) + h[rb][qd * 4 + 0], fmaf((float)acc2[rb][qd * 4 + 1], m.y, bs.y) + h[rb][qd * 4 + 1],
                                     fmaf((float)acc2[rb][qd * 4 + 2], m.z, bs.z) + h[rb][qd * 4 + 2], fmaf((float)acc2[rb][qd * 4 + 3], m.w, bs.w) + h[rb][qd * 4 + 3]);
+            if (pix[rb] >= 0) *(float4*)(A.y + (size_t)pix[rb] * C + n0) = o4;
+            if (TAPS && valid[rb]) {
+                if (A.tap_acc_fc2) *(int4*)(A.tap_acc_fc2 + canon[rb] * C + n0) = make_int4(acc2[rb][qd * 4], acc2[rb][qd * 4 + 1], acc2[rb][qd * 4 + 2], acc2[rb][qd * 4 + 3]);
+                if (A.tap_y) *(float4*)(A.tap_y + canon[rb] * C + n0) = o4;
+            }
+        }
+}
+
+// ------------------------------------------------------------------ fused token kernel, wide form
+// For C >= 192: one workgroup per tile of 64 gathered rows (two 32-row blocks share every weight fragment, which
+// halves the L2 -> CU weight traffic per row), one wave per 32-channel block.  Built for a small register
+// footprint: the per-branch parameter block sits in LDS, the weight fragments of the whole kernel form ONE stream
+// per wave (projection block, then per chunk the FC1 block and the FC2 fragments) that is requested RING
+// fragments ahead across every phase boundary, and with twelve waves h is parked in the output map between the
+// first and the second residual (the same thread writes and re-reads the same address) instead of in registers.
+// The FFN runs in four chunks of NH hidden blocks: FC1 + GELU + quantize of a chunk goes to one of two LDS buffers,
+// then FC2 accumulates that chunk.
+template <int NH, bool TAPS>
+__global__ __launch_bounds__(NH * 64) void token_wide_kernel(Geom G, TokArgs A)
+{
+    constexpr int C = NH * 32, KS = NH, HB = 4 * NH, F = 4 * C, NT = NH * 64, RB = 2;
+    constexpr int RING = NH == 6 ? 6 : 8;                              // fragments in flight per wave
+    constexpr bool PARK_H = NH >= 12 && !TAPS;                         // taps need h of padded tokens too, which have no pixel
+    static_assert((2 * KS) % RING == 0 && RING <= KS, "phases 2k start at ring slot 0, phases 2k+1 at slot KS % RING");
+    constexpr int SLOT_ODD = KS % RING;
+    using PR = TokPrm<C>;
+    __shared__ v4i actf[RB * KS * 64];                                 // [row block][k slab][lane]
+    __shared__ v4i gs[2][NH * RB * 64];                                // [buffer][hidden block of the chunk][row block][lane]
+    __shared__ double part[2][NH][32 * RB];
+    __shared__ __attribute__((aligned(16))) float prm[PR::WORDS];
+    __shared__ float4 gtab[GELU_K];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, g = lane >> 5;
+    const int row_base = blockIdx.x * (32 * RB);
+    const int branch = row_base >= G.base_lo ? 1 : 0;                 // a tile never straddles the regions: scalar
+    const int nb = wave;
+    const int* prmi = (const int*)prm;
+    // The wave's weight stream, phase by phase (every phase has KS = NH fragments): projection block, FC1 block of
+    // chunk 0, then per chunk c = 1..3 the FC1 block of chunk c followed by the FC2 fragments of chunk c-1, and the
+    // FC2 fragments of chunk 3 at the end.  FC2 of a chunk is issued one chunk late so that its matrix work runs
+    // under the GELU arithmetic of the next chunk.
+    const v4i* wproj = A.Wproj + (size_t)nb * KS * 64 + lane;
+    auto w1_of = [&](int chunk) { return A.W1 + ((size_t)(chunk * NH + wave) * KS) * 64 + lane; };
+    auto w2_of = [&](int chunk) { return A.W2 + ((size_t)nb * HB + chunk * NH) * 64 + lane; };
+    v4i ring[RING];
+#pragma unroll
+    for (int d = 0; d < RING; ++d) ring[d] = wproj[d * 64];            // the stream starts before anything else
+    int pix[RB];
+    bool valid[RB];
+    size_t canon[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int row = row_base + rb * 32 + j;
+        valid[rb] = branch ? (row - G.base_lo < G.rows_lo) : (row < G.rows_hi);
+        pix[rb] = valid[rb] ? A.row_pix[row] : -1;
+        canon[rb] = (TAPS && valid[rb]) ? (size_t)A.row_canon[row] : 0;
+    }
+    // stage the attention codes of the tile: piece p = (row r, 16-byte chunk q) -> fragment (r/32, q/2), lane (r%32, q%2)
+    for (int p = tid; p < 32 * RB * (C / 16); p += NT) {
+        const int r = p / (C / 16), q = p - r * (C / 16);
+        actf[((r >> 5) * KS + (q >> 1)) * 64 + (q & 1) * 32 + (r & 31)] = *(const v4i*)(A.ao + (size_t)(row_base + r) * C + q * 16);
+    }
+    {
+        const float4* psrc = (const float4*)A.params[branch];
+        for (int p = tid; p < PR::WORDS / 4; p += NT) ((float4*)prm)[p] = psrc[p];
+    }
+    gelu_stage_table(gtab, A.gelu_tab, tid, NT);
+    // acc[rb] += W * operand^T over one phase.  Weights come from the ring (slot0 = ring slot of the phase's first
+    // fragment); after fragment i is used, the fragment RING places further down the stream is requested: from this
+    // phase (cur) or from the start of the next one (nxt, NULL at the end of the stream).  Operand fragment i of
+    // row block rb: b[(rb*rb_stride + i*i_stride)*64 + lane].
+    auto run = [&](int slot0, const v4i* cur, const v4i* nxt, const v4i* b, int rb_stride, int i_stride, v16i* acc) {
+#pragma unroll
+        for (int i = 0; i < KS; ++i) {
+            const v4i wv = ring[(slot0 + i) % RING];
+            if (i + RING < KS) ring[(slot0 + i) % RING] = cur[(i + RING) * 64];
+            else if (nxt) ring[(slot0 + i) % RING] = nxt[(i + RING - KS) * 64];
+            acc[0] = mfma32(wv, b[(i * i_stride) * 64 + lane], acc[0]);
+            acc[1] = mfma32(wv, b[(rb_stride + i * i_stride) * 64 + lane], acc[1]);
+        }
+    };
+    auto start = [&](v16i* acc, int off) {                             // accumulators start at -zp * colsum
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            const int4 t4 = *(const int4*)(prmi + off + qd * 8 + g * 4);
+            acc[0][qd * 4 + 0] = t4.x; acc[0][qd * 4 + 1] = t4.y; acc[0][qd * 4 + 2] = t4.z; acc[0][qd * 4 + 3] = t4.w;
+        }
+        acc[1] = acc[0];
+    };
+    float4 sc[RB][4];                                                  // shortcut of the first residual, in flight during the projection
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd)
+            sc[rb][qd] = pix[rb] >= 0 ? *(const float4*)(A.x + (size_t)pix[rb] * C + nb * 32 + qd * 8 + g * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();                                                  // staged codes, parameters and table visible
+    float h[RB][16];
+    {   // output projection + first residual
+        v16i acc[RB];
+        start(acc, PR::P_NC + nb * 32);
+        run(0, wproj, w1_of(0), actf, KS, 1, acc);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                const int n0 = nb * 32 + qd * 8 + g * 4;
+                const float4 m = *(const float4*)(prm + PR::P_M + n0), bs = *(const float4*)(prm + PR::P_B + n0);
+                h[rb][qd * 4 + 0] = fmaf((float)acc[rb][qd * 4 + 0], m.x, bs.x) + sc[rb][qd].x;
+                h[rb][qd * 4 + 1] = fmaf((float)acc[rb][qd * 4 + 1], m.y, bs.y) + sc[rb][qd].y;
+                h[rb][qd * 4 + 2] = fmaf((float)acc[rb][qd * 4 + 2], m.z, bs.z) + sc[rb][qd].z;
+                h[rb][qd * 4 + 3] = fmaf((float)acc[rb][qd * 4 + 3], m.w, bs.w) + sc[rb][qd].w;
+                if (PARK_H && pix[rb] >= 0)
+                    *(float4*)(A.y + (size_t)pix[rb] * C + n0) = make_float4(h[rb][qd * 4], h[rb][qd * 4 + 1], h[rb][qd * 4 + 2], h[rb][qd * 4 + 3]);
+                if (TAPS && valid[rb]) {
+                    if (A.tap_acc_proj) *(int4*)(A.tap_acc_proj + canon[rb] * C + n0) = make_int4(acc[rb][qd * 4], acc[rb][qd * 4 + 1], acc[rb][qd * 4 + 2], acc[rb][qd * 4 + 3]);
+                    if (A.tap_h) *(float4*)(A.tap_h + canon[rb] * C + n0) = make_float4(h[rb][qd * 4], h[rb][qd * 4 + 1], h[rb][qd * 4 + 2], h[rb][qd * 4 + 3]);
+                }
+            }
+    }
+    {   // LN2: binary64 partial sums per (wave, token) through LDS, then normalise and quantize
+        float mean[RB];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            double s = 0.0;
+#pragma unroll
+            for (int r = 0; r < 16; r += 4) s += ((double)h[rb][r] + (double)h[rb][r + 1]) + ((double)h[rb][r + 2] + (double)h[rb][r + 3]);
+            s += __shfl_xor(s, 32, 64);
+            if (g == 0) part[0][wave][rb * 32 + j] = s;
+        }
+        __syncthreads();                                              // also: every wave is done reading the attention codes
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            double tot = 0.0;
+#pragma unroll
+            for (int w2i = 0; w2i < NH; ++w2i) tot += part[0][w2i][rb * 32 + j];
+            mean[rb] = (float)(tot / (double)C);
+            double q = 0.0;
+#pragma unroll
+            for (int r = 0; r < 16; r += 4) {
+                double a = (double)h[rb][r] - (double)mean[rb], b = (double)h[rb][r + 1] - (double)mean[rb];
+                double c = (double)h[rb][r + 2] - (double)mean[rb], d = (double)h[rb][r + 3] - (double)mean[rb];
+                q += (a * a + b * b) + (c * c + d * d);
+            }
+            q += __shfl_xor(q, 32, 64);
+            if (g == 0) part[1][wave][rb * 32 + j] = q;
+        }
+        __syncthreads();
+        const QDev qa = A.q_fc1in[branch];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            double tot = 0.0;
+#pragma unroll
+            for (int w2i = 0; w2i < NH; ++w2i) tot += part[1][w2i][rb * 32 + j];
+            const float var = (float)(tot / (double)C);
+            const float rstd = 1.0f / sqrtf(var + A.eps);
+            int wd[4];
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                const int n0 = nb * 32 + qd * 8 + g * 4;
+                const float4 gm = *(const float4*)(prm + PR::LN_G + n0), bt = *(const float4*)(prm + PR::LN_B + n0);
+                wd[qd] = pack4(quant_code(fmaf((h[rb][qd * 4 + 0] - mean[rb]) * rstd, gm.x, bt.x), qa),
+                               quant_code(fmaf((h[rb][qd * 4 + 1] - mean[rb]) * rstd, gm.y, bt.y), qa),
+                               quant_code(fmaf((h[rb][qd * 4 + 2] - mean[rb]) * rstd, gm.z, bt.z), qa),
+                               quant_code(fmaf((h[rb][qd * 4 + 3] - mean[rb]) * rstd, gm.w, bt.w), qa));
+                if (TAPS && valid[rb] && A.tap_a2) *(int*)(A.tap_a2 + canon[rb] * C + n0) = wd[qd];
+            }
+            actf[(rb * KS + nb) * 64 + lane] = (v4i){wd[0], wd[1], wd[2], wd[3]};   // k slab nb, byte r = channel 32nb + mfma_row(r,g)
+        }
+    }
+    __syncthreads();
+    v16i acc2[RB];
+    start(acc2, PR::F2_NC + nb * 32);
+    const QDev qg = A.q_fc2in[branch];
+    // GELU + quantize of the FC1 sums of hidden block ch*NH + wave -> LDS buffer ch & 1
+    auto gelu_chunk = [&](int ch, const v16i* acc) {
+        const int hb = ch * NH + wave;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            int wd[4];
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                const int n0 = hb * 32 + qd * 8 + g * 4;
+                const float4 m = *(const float4*)(prm + PR::F1_M + n0), bs = *(const float4*)(prm + PR::F1_B + n0);
+                wd[qd] = pack4(quant_code(gelu_scaled(fmaf((float)acc[rb][qd * 4 + 0], m.x, bs.x), gtab), qg),
+                               quant_code(gelu_scaled(fmaf((float)acc[rb][qd * 4 + 1], m.y, bs.y), gtab), qg),
+                               quant_code(gelu_scaled(fmaf((float)acc[rb][qd * 4 + 2], m.z, bs.z), gtab), qg),
+                               quant_code(gelu_scaled(fmaf((float)acc[rb][qd * 4 + 3], m.w, bs.w), gtab), qg));
+                if (TAPS && valid[rb]) {
+                    if (A.tap_acc_fc1) *(int4*)(A.tap_acc_fc1 + canon[rb] * F + n0) = make_int4(acc[rb][qd * 4], acc[rb][qd * 4 + 1], acc[rb][qd * 4 + 2], acc[rb][qd * 4 + 3]);
+                    if (A.tap_g) *(int*)(A.tap_g + canon[rb] * F + n0) = wd[qd];
+                }
+            }
+            gs[ch & 1][(wave * RB + rb) * 64 + lane] = (v4i){wd[0], wd[1], wd[2], wd[3]};
+        }
+    };
+    {   // chunk 0: FC1 + GELU
+        v16i acc[RB];
+        start(acc, PR::F1_NC + wave * 32);
+        run(SLOT_ODD, w1_of(0), w1_of(1), actf, KS, 1, acc);
+        gelu_chunk(0, acc);
+    }
+    __syncthreads();                                                  // chunk 0 of the hidden codes complete
+#pragma unroll 1
+    for (int ch = 1; ch < 4; ++ch) {
+        v16i acc[RB];
+        start(acc, PR::F1_NC + (ch * NH + wave) * 32);
+        run(0, w1_of(ch), w2_of(ch - 1), actf, KS, 1, acc);                                   // FC1 of chunk ch
+        run(SLOT_ODD, w2_of(ch - 1), ch < 3 ? w1_of(ch + 1) : w2_of(3), gs[(ch - 1) & 1], 1, RB, acc2);   // FC2 of chunk ch-1, under ...
+        gelu_chunk(ch, acc);                                                                  // ... this arithmetic
+        __syncthreads();                                              // chunk ch complete, chunk ch-1 no longer read
+    }
+    run(0, w2_of(3), nullptr, gs[1], 1, RB, acc2);                     // FC2 of the last chunk
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {   // second residual + scatter
+            const int n0 = nb * 32 + qd * 8 + g * 4;
+            const float4 m = *(const float4*)(prm + PR::F2_M + n0), bs = *(const float4*)(prm + PR::F2_B + n0);
+            float4 hh = make_float4(h[rb][qd * 4], h[rb][qd * 4 + 1], h[rb][qd * 4 + 2], h[rb][qd * 4 + 3]);
+            if (PARK_H) hh = pix[rb] >= 0 ? *(const float4*)(A.y + (size_t)pix[rb] * C + n0) : make_float4(0.f, 0.f, 0.f, 0.f);
+            float4 o4 = make_float4(fmaf((float)acc2[rb][qd * 4 + 0], m.x, bs.x) + hh.x, fmaf((float)acc2[rb][qd * 4 + 1], m.y, bs.y) + hh.y,
+                                    fmaf((float)acc2[rb][qd * 4 + 2], m.z, bs.z) + hh.z, fmaf((float)acc2[rb][qd * 4 + 3], m.w, bs.w) + hh.w);
             if (pix[rb] >= 0) *(float4*)(A.y + (size_t)pix[rb] * C + n0) = o4;
             if (TAPS && valid[rb]) {
                 if (A.tap_acc_fc2) *(int4*)(A.tap_acc_fc2 + canon[rb] * C + n0) = make_int4(acc2[rb][qd * 4], acc2[rb][qd * 4 + 1], acc2[rb][qd * 4 + 2], acc2[rb][qd * 4 + 3]);
@@ -1385,23 +1624,13 @@ void launch_token(const Geom& G, const TokArgs& A, hipStream_t st)
     if (A.taps) hipLaunchKernelGGL((token_kernel<NH, true>), dim3(G.rows_total / 32), dim3(NH * 64), 0, st, G, A); \
     else hipLaunchKernelGGL((token_kernel<NH, false>), dim3(G.rows_total / 32), dim3(NH * 64), 0, st, G, A);      \
     break
-    // few rows (less than one 64-row tile for every second CU): 32-row tiles, twice the workgroups
-    const bool small = G.rows_total / 64 <= TOKEN_STREAM_SMALL;
-#define STREAM_CASE(NH)                                                                                                             \
-    if (small) {                                                                                                                    \
-        if (A.taps) hipLaunchKernelGGL((token_stream_kernel<NH, true, 1>), dim3(G.rows_total / 32), dim3(NH * 64), 0, st, G, A);   \
-        else hipLaunchKernelGGL((token_stream_kernel<NH, false, 1>), dim3(G.rows_total / 32), dim3(NH * 64), 0, st, G, A);         \
-    } else {                                                                                                                        \
-        if (A.taps) hipLaunchKernelGGL((token_stream_kernel<NH, true, 2>), dim3(G.rows_total / 64), dim3(NH * 64), 0, st, G, A);   \
-        else hipLaunchKernelGGL((token_stream_kernel<NH, false, 2>), dim3(G.rows_total / 64), dim3(NH * 64), 0, st, G, A);         \
-    }                                                                                                                               \
-    break
-    if (NHr >= TOKEN_STREAM_FROM) {
-        switch (NHr) {
-            case 6: STREAM_CASE(6);
-            case 8: STREAM_CASE(8);
-            default: STREAM_CASE(12);
-        }
+    // twelve heads: the wide 64-row form once there are enough tiles to give every second CU one, else 32-row tiles
+    if (NHr == 12 && G.rows_total / 64 > TOKEN_STREAM_SMALL) {
+        if (A.taps) hipLaunchKernelGGL((token_wide_kernel<12, true>), dim3(G.rows_total / 64), dim3(12 * 64), 0, st, G, A);
+        else hipLaunchKernelGGL((token_wide_kernel<12, false>), dim3(G.rows_total / 64), dim3(12 * 64), 0, st, G, A);
+    } else if (NHr >= TOKEN_STREAM_FROM) {
+        if (A.taps) hipLaunchKernelGGL((token_stream_kernel<12, true, 1>), dim3(G.rows_total / 32), dim3(12 * 64), 0, st, G, A);
+        else hipLaunchKernelGGL((token_stream_kernel<12, false, 1>), dim3(G.rows_total / 32), dim3(12 * 64), 0, st, G, A);
     } else {
         switch (NHr) {
             case 3: TOK_CASE(3);
@@ -1411,7 +1640,6 @@ void launch_token(const Geom& G, const TokArgs& A, hipStream_t st)
         }
     }
 #undef TOK_CASE
-#undef STREAM_CASE
 }
 
 void launch_attn(const Geom& G, const AttnArgs& A, hipStream_t st)
