@@ -127,6 +127,7 @@ struct Linear {           // one shadow layer prepared for the device
     float* m[2] = {nullptr, nullptr};
     float* bias[2] = {nullptr, nullptr};
     int* negcorr[2] = {nullptr, nullptr};
+    std::vector<int> colsum;   // sum_k W[n,k], kept on the host
 };
 
 }  // namespace
@@ -145,6 +146,7 @@ struct mixaq_block {
     float m2[2], m_o[2];
     float* tok_params[2] = {nullptr, nullptr};   // parameter blocks of the fused token kernel
     float* win_params[2] = {nullptr, nullptr};   // parameter blocks of the fused window kernel
+    int ao_pack = 0;           // packing of the low branch's attention-output codes between the two fused kernels
     const float4* gelu_tab = nullptr;            // cubic coefficients of the pinned GELU
     size_t ws_bytes = 0;
     size_t ws_fused_bytes = 0; // what the two fused kernels alone need
@@ -211,6 +213,7 @@ int prepare_linear(mixaq_block* blk, Linear& L, const int8_t* w_dev, const float
             }
     L.K = K;
     L.N = N;
+    L.colsum = colsum;
     int8_t* wp = nullptr;
     if ((rc = upload(blk->owned, packed, &wp))) return rc;
     L.Wp = (v4i*)wp;
@@ -363,6 +366,7 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, co
         wa.x = x; wa.perm = perm; wa.scores = in_kernel_select ? scores : nullptr; wa.reverse = 0; wa.perm_out = perm_out ? perm_out : ws.perm;
         wa.y = y; wa.eps = d.ln_eps; wa.Wqkv = blk->qkv.Wp; wa.bias2 = blk->bias2; wa.out = ws.ao;
         wa.row_pix = ws.row_pix; wa.row_canon = ws.row_canon;
+        wa.out_pack = ft ? blk->ao_pack : 0;
         for (int br = 0; br < 2; ++br) {
             wa.params[br] = blk->win_params[br]; wa.q_in[br] = blk->q_in[br];
             for (int k = 0; k < 3; ++k) wa.q_qkv[br][k] = blk->q_qkv[br][k];
@@ -399,6 +403,7 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, co
         TokArgs ta = {};
         ta.ao = ws.ao; ta.x = x; ta.y = y; ta.row_pix = ws.row_pix; ta.row_canon = ws.row_canon; ta.eps = d.ln_eps;
         ta.Wproj = blk->proj.Wp; ta.W1 = blk->fc1.Wp_reg; ta.W2 = blk->fc2.Wp_reg;
+        ta.ao_pack = blk->ao_pack;
         for (int br = 0; br < 2; ++br) {
             ta.params[br] = blk->tok_params[br];
             ta.q_fc1in[br] = blk->q_fc1in[br]; ta.q_fc2in[br] = blk->q_fc2in[br];
@@ -582,6 +587,9 @@ int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* 
             if ((rc = gather_block({{b->ln_gamma[0][br], C}, {b->ln_beta[0][br], C}, {b->qkv.m[br], 3 * C}, {b->qkv.bias[br], 3 * C},
                                     {b->qkv.negcorr[br], 3 * C}}, &b->win_params[br])))
                 return bail(rc);
+    // Both fused kernels present: the low branch's attention-output codes cross between them packed (two or four
+    // per byte, offset-binary); the projection of packed rows then starts at -(zp + offset) * colsum.
+    if (b->fused_window && b->fused_token) b->ao_pack = pack_mode(desc->act_bits_low);
     if (b->fused_token) {     // parameter blocks of the token kernel: device-to-device gathers of what was just uploaded
         for (int br = 0; br < 2; ++br) {
             std::vector<float> blkp((size_t)8 * C + 3 * F);
@@ -594,6 +602,11 @@ int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* 
                 if (hipMemcpy(blkp.data() + off, pt.src, (size_t)pt.n * 4, hipMemcpyDeviceToHost) != hipSuccess)
                     return bail(fail(MIXAQ_E_HIP, "copy of a parameter block failed"));
                 off += pt.n;
+            }
+            if (br == 1 && b->ao_pack) {       // packed rows carry u = code + offset: the projection removes zp + offset
+                const int shift_by = branch[1].a_proj_in.zero_point + pack_offset(b->ao_pack);
+                int* nc = (int*)blkp.data() + 2 * C;
+                for (int n = 0; n < C; ++n) nc[n] = -shift_by * b->proj.colsum[n];
             }
             if ((rc = upload(b->owned, blkp, &b->tok_params[br]))) return bail(rc);
         }

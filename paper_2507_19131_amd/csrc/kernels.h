@@ -83,6 +83,7 @@ struct WinArgs {                     // fused window kernel (gather + LN1 + QKV 
     float m2[2], m_o[2];
     QDev qp[2], qo[2];
     int8_t* out;                     // attention output codes [rows,C]
+    int out_pack;                    // 0: int8 containers; 1, 2: the low region's rows packed (see unpack_codes)
     int* row_pix;
     int* row_canon;
     int8_t* tap_a1; int32_t* tap_acc; int8_t* tap_qkv; int32_t* tap_s; int8_t* tap_p; int32_t* tap_o; int8_t* tap_code;
@@ -92,6 +93,7 @@ struct WinArgs {                     // fused window kernel (gather + LN1 + QKV 
 
 struct TokArgs {                     // fused token kernel (proj + LN2 + FFN + scatter)
     const int8_t* ao;                // [rows,C]
+    int ao_pack;                     // as WinArgs::out_pack
     const float* x;
     float* y;
     const int* row_pix;

@@ -455,25 +455,39 @@ __device__ __forceinline__ void attention_core(const v4i (&qf)[2], const v4i (&k
 template <bool TAPS>
 __device__ __forceinline__ void attention_store(const v16i (&o)[2], const int* csum, const QDev& qp, const QDev& qo, float m_o,
                                                 int j, int g, int head, int C, int8_t* out, int row0, int32_t* tap_o,
-                                                int8_t* tap_code, size_t canon_row0)
+                                                int8_t* tap_code, size_t canon_row0, int pack = 0)
 {
 #pragma unroll
     for (int ib = 0; ib < 2; ++ib) {
         const int qi = ib * 32 + j;
         if (qi < TOK) {
+            int code[4];
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 const int d0 = qd * 8 + g * 4;
                 const int4 cz = *(const int4*)(csum + d0);
                 int a0 = o[ib][qd * 4 + 0] - qp.zp * cz.x, a1 = o[ib][qd * 4 + 1] - qp.zp * cz.y;
                 int a2 = o[ib][qd * 4 + 2] - qp.zp * cz.z, a3 = o[ib][qd * 4 + 3] - qp.zp * cz.w;
-                int code = pack4(quant_code((float)a0 * m_o, qo), quant_code((float)a1 * m_o, qo),
+                code[qd] = pack4(quant_code((float)a0 * m_o, qo), quant_code((float)a1 * m_o, qo),
                                  quant_code((float)a2 * m_o, qo), quant_code((float)a3 * m_o, qo));
                 const int ch = head * HD + d0;
-                *(int*)(out + (size_t)(row0 + qi) * C + ch) = code;
+                if (pack == 0) *(int*)(out + (size_t)(row0 + qi) * C + ch) = code[qd];
                 size_t ci = (canon_row0 + qi) * C + ch;
                 if (TAPS && tap_o) *(int4*)(tap_o + ci) = make_int4(a0, a1, a2, a3);
-                if (TAPS && tap_code) *(int*)(tap_code + ci) = code;
+                if (TAPS && tap_code) *(int*)(tap_code + ci) = code[qd];
+            }
+            if (pack == 1) {                       // out = first packed row of the region, row0 = row inside it
+                int8_t* rowp = out + (size_t)(row0 + qi) * (C / 2) + head * 16 + g * 4;
+#pragma unroll
+                for (int p = 0; p < 2; ++p) {
+                    const int lo = (code[2 * p] ^ 0x08080808) & 0x0f0f0f0f, hi = (code[2 * p + 1] ^ 0x08080808) & 0x0f0f0f0f;
+                    *(int*)(rowp + p * 8) = lo | (hi << 4);
+                }
+            } else if (pack == 2) {
+                int w = 0;
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) w |= ((code[qd] ^ 0x02020202) & 0x03030303) << (2 * qd);
+                *(int*)(out + (size_t)(row0 + qi) * (C / 4) + head * 8 + g * 4) = w;
             }
         }
     }
@@ -852,7 +866,10 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
     attention_core<TAPS>(qk[0], qk[1], vt, core, j, g, o);
     __builtin_amdgcn_s_waitcnt(0);
     __builtin_amdgcn_wave_barrier();
-    attention_store<TAPS>(o, csum[wave], core.qp, A.qo[branch], A.m_o[branch], j, g, head, C, A.out, row0, A.tap_o, A.tap_code, canon_row0);
+    const int pack = branch ? A.out_pack : 0;                            // the low region's rows may be packed (dense, after the high region)
+    if (pack) attention_store<TAPS>(o, csum[wave], core.qp, A.qo[branch], A.m_o[branch], j, g, head, C, A.out + (size_t)G.base_lo * C,
+                                    row0 - G.base_lo, A.tap_o, A.tap_code, canon_row0, pack);
+    else attention_store<TAPS>(o, csum[wave], core.qp, A.qo[branch], A.m_o[branch], j, g, head, C, A.out, row0, A.tap_o, A.tap_code, canon_row0);
 }
 
 // ------------------------------------------------------------------ fused token kernel
@@ -900,11 +917,16 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(NH <= 4
     const bool tap_ok = TAPS && valid;
     v4i aof[KS], wpf[KS], w1f[KS];
     {
+        const int pack = branch ? A.ao_pack : 0;                       // packed low-branch codes: scalar per tile
         const int8_t* ap = A.ao + (size_t)row * C + g * 16;
+        const int8_t* pp = A.ao + (size_t)G.base_lo * C + (size_t)(row - G.base_lo) * (C >> pack);
         const v4i* wp = A.Wproj + (size_t)nb * KS * 64 + lane;
         const v4i* w1 = A.W1 + (size_t)wave * KS * 64 + lane;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) { aof[ks] = *(const v4i*)(ap + ks * 32); wpf[ks] = wp[ks * 64]; w1f[ks] = w1[ks * 64]; }
+        for (int ks = 0; ks < KS; ++ks) {
+            aof[ks] = pack ? unpack_codes(pp, pack, ks, g) : *(const v4i*)(ap + ks * 32);
+            wpf[ks] = wp[ks * 64]; w1f[ks] = w1[ks * 64];
+        }
     }
     gelu_stage_table(gtab, A.gelu_tab, tid, NT);
     const float4* gelu_lds = gtab;
@@ -1090,9 +1112,12 @@ __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A
         canon[rb] = (TAPS && valid[rb]) ? (size_t)A.row_canon[row] : 0;
     }
     // stage the attention codes of the tile: piece p = (row r, 16-byte chunk q) -> fragment (r/32, q/2), lane (r%32, q%2)
+    const int pack = branch ? A.ao_pack : 0;                           // packed low-branch codes: scalar per tile
     for (int p = tid; p < 32 * RB * (C / 16); p += NT) {
         const int r = p / (C / 16), q = p - r * (C / 16);
-        actf[((r >> 5) * KS + (q >> 1)) * 64 + (q & 1) * 32 + (r & 31)] = *(const v4i*)(A.ao + (size_t)(row_base + r) * C + q * 16);
+        actf[((r >> 5) * KS + (q >> 1)) * 64 + (q & 1) * 32 + (r & 31)] =
+            pack ? unpack_codes(A.ao + (size_t)G.base_lo * C + (size_t)(row_base - G.base_lo + r) * (C >> pack), pack, q >> 1, q & 1)
+                 : *(const v4i*)(A.ao + (size_t)(row_base + r) * C + q * 16);
     }
     gelu_stage_table(gtab, A.gelu_tab, tid, NT);
     // acc[rb] += W(fragments wp[0], wp[64], ...) * operand fragments b[(rb * stride_rb + i) * 64 + lane]
@@ -1310,9 +1335,12 @@ __global__ __launch_bounds__(NH * 64) void token_wide_kernel(Geom G, TokArgs A)
         canon[rb] = (TAPS && valid[rb]) ? (size_t)A.row_canon[row] : 0;
     }
     // stage the attention codes of the tile: piece p = (row r, 16-byte chunk q) -> fragment (r/32, q/2), lane (r%32, q%2)
+    const int pack = branch ? A.ao_pack : 0;                           // packed low-branch codes: scalar per tile
     for (int p = tid; p < 32 * RB * (C / 16); p += NT) {
         const int r = p / (C / 16), q = p - r * (C / 16);
-        actf[((r >> 5) * KS + (q >> 1)) * 64 + (q & 1) * 32 + (r & 31)] = *(const v4i*)(A.ao + (size_t)(row_base + r) * C + q * 16);
+        actf[((r >> 5) * KS + (q >> 1)) * 64 + (q & 1) * 32 + (r & 31)] =
+            pack ? unpack_codes(A.ao + (size_t)G.base_lo * C + (size_t)(row_base - G.base_lo + r) * (C >> pack), pack, q >> 1, q & 1)
+                 : *(const v4i*)(A.ao + (size_t)(row_base + r) * C + q * 16);
     }
     {
         const float4* psrc = (const float4*)A.params[branch];

@@ -98,6 +98,31 @@ __device__ __forceinline__ float gelu_scaled(float xs, const float4* lds)
     return fmaxf(xs, 0.0f) - h;
 }
 
+// ---- packed sub-byte codes (tensors that cross a kernel boundary) ---------------------------------
+// The attention-output codes of the LOW branch travel packed when its bit width allows: two codes per byte
+// (widths 3 and 4) or four per byte (width 2), stored offset-binary (u = code + PACK_OFFSET, never negative) so
+// that unpacking is a shift and a mask; the consumer removes the offset together with the zero point
+// (sum_k u_k w_k - (zp + offset) * sum_k w_k).  The layout is chosen so that the producer (a lane of the window
+// kernel holds, per query and head, the dims qd*8 + g*4 + e, qd = 0..3, e = 0..3, of its half g) packs without
+// leaving the lane, and the consumer (a lane needs 16 consecutive channels) reads 8 contiguous bytes:
+//   pack 1 (nibbles), row stride C/2, per head 16 bytes: dword p*2 + g (p = 0,1), byte e:
+//       low nibble = u(dim p*16 + g*4 + e), high nibble = u(dim p*16 + 8 + g*4 + e)
+//   pack 2 (two-bit fields), row stride C/4, per head 8 bytes: dword g, byte e, bits 2qd..2qd+1 = u(dim qd*8 + g*4 + e)
+__host__ __device__ constexpr int pack_mode(int bits) { return bits <= 2 ? 2 : bits <= 4 ? 1 : 0; }
+__host__ __device__ constexpr int pack_offset(int mode) { return mode == 2 ? 2 : mode == 1 ? 8 : 0; }
+
+// the 16 codes (offset-binary, one per byte, in channel order) of channels 32*ks + 16*half .. +15 of one packed row
+__device__ __forceinline__ v4i unpack_codes(const int8_t* packed_row, int mode, int ks, int half)
+{
+    if (mode == 1) {
+        const int2 w = *(const int2*)(packed_row + ks * 16 + half * 8);
+        return (v4i){w.x & 0x0f0f0f0f, w.y & 0x0f0f0f0f, (w.x >> 4) & 0x0f0f0f0f, (w.y >> 4) & 0x0f0f0f0f};
+    }
+    const int2 w = *(const int2*)(packed_row + ks * 8);
+    const int s = half * 4;
+    return (v4i){(w.x >> s) & 0x03030303, (w.y >> s) & 0x03030303, (w.x >> (s + 2)) & 0x03030303, (w.y >> (s + 2)) & 0x03030303};
+}
+
 // D[32x32] += A[32 x 32k] * B[32k x 32]; lane l supplies row (A) / column (B) l%32 and
 // the 16 k-values of half l/32; D register r of lane l is row (r/4)*8 + (l/32)*4 + r%4,
 // column l%32.
