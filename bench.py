@@ -176,21 +176,13 @@ class Stage:
         names = [M.mixaq_kernel_name(i) for i in range(M.NUM_KERNELS)]
         acc = {n: 0.0 for n in names}
         launches = {n: 0 for n in names}
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         for _ in range(prof_steps):
-            ev0.record()
-            for _r in range(rep):
-                M.mixaq_score_windows(self.blocks[0], self.x, self.scores)
-            ev1.record()
-            ev1.synchronize()
-            acc["score"] += ev0.elapsed_time(ev1) / rep
-            launches["score"] += 1
             cur = self.x
             for i, blk in enumerate(self.blocks):
                 dst = self.bufs[i % 2]
-                if i == 0:
-                    ms = M.mixaq_block_forward_profile(blk, cur, None, self.k_high, dst, self.ws, repeats=rep, scores=self.scores)
-                else:
+                if i == 0:      # scores and selection inside the call: the score kernel is timed like the others
+                    ms = M.mixaq_block_forward_profile(blk, cur, None, self.k_high, dst, self.ws, repeats=rep)
+                else:           # self.perm holds the stage's list since the timed steps
                     ms = M.mixaq_block_forward_profile(blk, cur, self.perm, self.k_high, dst, self.ws, repeats=rep)
                 cur = dst
                 for n, v in ms.items():
@@ -289,6 +281,15 @@ def backbone_chain(M, synth, torch, steps):
                 note="patch embedding + 4 stages + 3 patch mergings per image; the int-TOPS count the blocks' operations only")
 
 
+def calibration_copy(torch, dev):
+    """A plain copy of known size, so that a counter run of this same command can calibrate FETCH_SIZE /
+    WRITE_SIZE against bytes (64 MiB read + 64 MiB written)."""
+    calib_src = torch.empty(64 * 1024 * 1024, dtype=torch.uint8, device=dev)
+    calib_dst = torch.empty_like(calib_src)
+    calib_dst.copy_(calib_src)
+    torch.cuda.synchronize()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -296,6 +297,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=500)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--headline-only", action="store_true", help="skip configs 1, 3, 4, 5")
+    ap.add_argument("--workload", default=None, help="run ONE workload's stage only (cfg1..cfg5), e.g. under rocprofv3")
+    ap.add_argument("--stage", type=int, default=0, help="stage of --workload")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path has no collectives); run with --gpus 1",
@@ -314,6 +317,18 @@ def main():
     if not args.no_cpu_baseline:
         sys.path.insert(0, os.path.join(ROOT, "tests"))
         import oracle_api as O              # the oracle is used for the cpu_baseline legs only
+
+    if args.workload:            # one stage on its own: what a profiler run of a single workload executes
+        wln = synth.workload(args.workload)
+        stg = Stage(M, synth, torch, wln, args.stage, wln["keep"][len(wln["keep"]) // 2])
+        stg.spin_up()
+        ms = stg.time_steps(args.steps, args.warmup)
+        s = stg.summary(ms, stg.profile(min(args.steps, 50)))
+        s.update(workload=args.workload, stage=args.stage, steps=args.steps, warmup=args.warmup)
+        stg.close()
+        calibration_copy(torch, dev)
+        print(json.dumps(s))
+        return 0
 
     # ---------------------------------------------------------------- headline: config 2
     wl = synth.workload("cfg2")
@@ -402,12 +417,7 @@ def main():
                int_tops=round(int_tops, 3), pct_int8_mfma_peak=round(100 * int_tops / PEAK_INT8_TOPS, 3),
                ms_per_block=round(ms_per_step / 2, 5), frac_of_fused_ideal=round(value / ideal_windows_per_s(spec.C), 5),
                roofline=roofline, kernels=kernels, cpu_baseline=cpu, configs=configs)
-    # a plain copy of known size, so that a counter run of this same command can calibrate
-    # FETCH_SIZE / WRITE_SIZE against bytes (64 MiB read + 64 MiB written)
-    calib_src = torch.empty(64 * 1024 * 1024, dtype=torch.uint8, device=dev)
-    calib_dst = torch.empty_like(calib_src)
-    calib_dst.copy_(calib_src)
-    torch.cuda.synchronize()
+    calibration_copy(torch, dev)
     print(json.dumps(out))
     return 0
 

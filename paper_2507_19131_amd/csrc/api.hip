@@ -266,8 +266,8 @@ void make_geom(const mixaq_block* b, int k_hi, int k_lo, Geom* G)
     G->k_hi = k_hi; G->k_lo = k_lo; G->n_slots = b->d.B * (k_hi + k_lo);
     G->rows_hi = b->d.B * k_hi * TOK;
     G->rows_lo = b->d.B * G->k_lo * TOK;
-    G->base_lo = round_up(G->rows_hi, ROW_TILE);
-    G->rows_total = G->base_lo + round_up(G->rows_lo, ROW_TILE);
+    G->base_lo = round_up(G->rows_hi, REGION_ALIGN);
+    G->rows_total = G->base_lo + round_up(G->rows_lo, REGION_ALIGN);
 }
 
 struct Workspace {
@@ -611,7 +611,7 @@ int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* 
             if ((rc = upload(b->owned, blkp, &b->tok_params[br]))) return bail(rc);
         }
     }
-    b->rows_max = round_up(desc->B * b->nW * TOK, ROW_TILE) + ROW_TILE;
+    b->rows_max = round_up(desc->B * b->nW * TOK, REGION_ALIGN) + REGION_ALIGN;
     Workspace w;
     b->ws_bytes = carve(b, nullptr, &w);
     b->ws_fused_bytes = carve(b, nullptr, &w, true);

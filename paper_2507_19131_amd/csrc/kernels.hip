@@ -880,7 +880,10 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
 // Latency is hidden by issuing loads a phase ahead: the per-branch parameter block (epilogue
 // constants, LN2 affine) is staged in LDS once, weight fragments of the next MFMA chain are
 // requested before the current epilogue starts.
-constexpr int TOK_WAVES_PER_EU = 4;
+// waves per SIMD the token kernel is compiled for: two workgroups per CU with six or eight waves each (12 or 16
+// waves), four and five with four and three waves; measured: one more resident workgroup at eight waves takes the
+// kernel from 122 to 96 us on 70756 rows, five waves per SIMD at three or six waves per workgroup gain nothing
+constexpr int tok_waves_per_eu(int NH) { return NH == 6 ? 3 : 4; }
 // word offsets inside the parameter block of one branch (see TokArgs::params)
 template <int C> struct TokPrm {
     static constexpr int F = 4 * C;
@@ -889,12 +892,13 @@ template <int C> struct TokPrm {
 };
 
 template <int NH, bool TAPS>
-__global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(NH <= 4 ? TOK_WAVES_PER_EU : 3, NH <= 4 ? TOK_WAVES_PER_EU : 3))) void token_kernel(Geom G, TokArgs A)
+__global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(tok_waves_per_eu(NH), tok_waves_per_eu(NH)))) void token_kernel(Geom G, TokArgs A)
 {
     constexpr int C = NH * 32, KS = NH, HB = 4 * NH, F = 4 * C, NT = NH * 64;
     using PR = TokPrm<C>;
     constexpr int PV = PR::WORDS / 4, PVT = (PV + NT - 1) / NT;       // float4 of the block, per thread
     constexpr int D2 = 4;                                            // FC2 weight fragments in flight
+    constexpr bool EARLY_W1 = NH <= 6;                               // first FC1 weights requested at entry (register room permitting)
     __shared__ v4i a2s[KS * 64];
     __shared__ v4i gs[HB * 64];
     __shared__ double part[2][NH][32];
@@ -925,7 +929,8 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(NH <= 4
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             aof[ks] = pack ? unpack_codes(pp, pack, ks, g) : *(const v4i*)(ap + ks * 32);
-            wpf[ks] = wp[ks * 64]; w1f[ks] = w1[ks * 64];
+            wpf[ks] = wp[ks * 64];
+            if (EARLY_W1) w1f[ks] = w1[ks * 64];
         }
     }
     gelu_stage_table(gtab, A.gelu_tab, tid, NT);
@@ -949,6 +954,11 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(NH <= 4
         }
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) acc = mfma32(wpf[ks], aof[ks], acc);
+        if (!EARLY_W1) {                                              // wide blocks: the first FC1 weights follow the projection chain
+            const v4i* w1 = A.W1 + (size_t)wave * KS * 64 + lane;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) w1f[ks] = w1[ks * 64];
+        }
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
             const int n0 = nb * 32 + qd * 8 + g * 4;
@@ -1287,20 +1297,21 @@ __global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A
 }
 
 // ------------------------------------------------------------------ fused token kernel, wide form
-// For C >= 192: one workgroup per tile of 64 gathered rows (two 32-row blocks share every weight fragment, which
-// halves the L2 -> CU weight traffic per row), one wave per 32-channel block.  Built for a small register
+// For the wide stages: one workgroup per tile of 32*RB gathered rows (RB 32-row blocks share every weight fragment,
+// which divides the L2 -> CU weight traffic per row by RB: each wave streams weights nobody else uses, so bytes
+// in flight per CU, not bandwidth, bound that stream), one wave per 32-channel block.  Built for a small register
 // footprint: the per-branch parameter block sits in LDS, the weight fragments of the whole kernel form ONE stream
 // per wave (projection block, then per chunk the FC1 block and the FC2 fragments) that is requested RING
 // fragments ahead across every phase boundary, and with twelve waves h is parked in the output map between the
 // first and the second residual (the same thread writes and re-reads the same address) instead of in registers.
 // The FFN runs in four chunks of NH hidden blocks: FC1 + GELU + quantize of a chunk goes to one of two LDS buffers,
 // then FC2 accumulates that chunk.
-template <int NH, bool TAPS>
+template <int NH, int RB, bool TAPS>
 __global__ __launch_bounds__(NH * 64) void token_wide_kernel(Geom G, TokArgs A)
 {
-    constexpr int C = NH * 32, KS = NH, HB = 4 * NH, F = 4 * C, NT = NH * 64, RB = 2;
+    constexpr int C = NH * 32, KS = NH, HB = 4 * NH, F = 4 * C, NT = NH * 64;
     constexpr int RING = NH == 6 ? 6 : 8;                              // fragments in flight per wave
-    constexpr bool PARK_H = NH >= 12 && !TAPS;                         // taps need h of padded tokens too, which have no pixel
+    constexpr bool PARK_H = (NH >= 12 || RB >= 4) && !TAPS;          // taps need h of padded tokens too, which have no pixel
     static_assert((2 * KS) % RING == 0 && RING <= KS, "phases 2k start at ring slot 0, phases 2k+1 at slot KS % RING");
     constexpr int SLOT_ODD = KS % RING;
     using PR = TokPrm<C>;
@@ -1357,8 +1368,8 @@ __global__ __launch_bounds__(NH * 64) void token_wide_kernel(Geom G, TokArgs A)
             const v4i wv = ring[(slot0 + i) % RING];
             if (i + RING < KS) ring[(slot0 + i) % RING] = cur[(i + RING) * 64];
             else if (nxt) ring[(slot0 + i) % RING] = nxt[(i + RING - KS) * 64];
-            acc[0] = mfma32(wv, b[(i * i_stride) * 64 + lane], acc[0]);
-            acc[1] = mfma32(wv, b[(rb_stride + i * i_stride) * 64 + lane], acc[1]);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) acc[rb] = mfma32(wv, b[(rb * rb_stride + i * i_stride) * 64 + lane], acc[rb]);
         }
     };
     auto start = [&](v16i* acc, int off) {                             // accumulators start at -zp * colsum
@@ -1367,7 +1378,8 @@ __global__ __launch_bounds__(NH * 64) void token_wide_kernel(Geom G, TokArgs A)
             const int4 t4 = *(const int4*)(prmi + off + qd * 8 + g * 4);
             acc[0][qd * 4 + 0] = t4.x; acc[0][qd * 4 + 1] = t4.y; acc[0][qd * 4 + 2] = t4.z; acc[0][qd * 4 + 3] = t4.w;
         }
-        acc[1] = acc[0];
+#pragma unroll
+        for (int rb = 1; rb < RB; ++rb) acc[rb] = acc[0];
     };
     float4 sc[RB][4];                                                  // shortcut of the first residual, in flight during the projection
 #pragma unroll
@@ -1654,8 +1666,8 @@ void launch_token(const Geom& G, const TokArgs& A, hipStream_t st)
     break
     // twelve heads: the wide 64-row form once there are enough tiles to give every second CU one, else 32-row tiles
     if (NHr == 12 && G.rows_total / 64 > TOKEN_STREAM_SMALL) {
-        if (A.taps) hipLaunchKernelGGL((token_wide_kernel<12, true>), dim3(G.rows_total / 64), dim3(12 * 64), 0, st, G, A);
-        else hipLaunchKernelGGL((token_wide_kernel<12, false>), dim3(G.rows_total / 64), dim3(12 * 64), 0, st, G, A);
+        if (A.taps) hipLaunchKernelGGL((token_wide_kernel<12, 2, true>), dim3(G.rows_total / 64), dim3(12 * 64), 0, st, G, A);
+        else hipLaunchKernelGGL((token_wide_kernel<12, 2, false>), dim3(G.rows_total / 64), dim3(12 * 64), 0, st, G, A);
     } else if (NHr >= TOKEN_STREAM_FROM) {
         if (A.taps) hipLaunchKernelGGL((token_stream_kernel<12, true, 1>), dim3(G.rows_total / 32), dim3(12 * 64), 0, st, G, A);
         else hipLaunchKernelGGL((token_stream_kernel<12, false, 1>), dim3(G.rows_total / 32), dim3(12 * 64), 0, st, G, A);

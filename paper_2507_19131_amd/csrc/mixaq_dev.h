@@ -13,7 +13,8 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int WS = 7;            // window side
 constexpr int TOK = 49;          // tokens per window
 constexpr int HD = 32;           // head dimension = one 32-wide MFMA block
-constexpr int ROW_TILE = 64;     // rows per GEMM tile; branch regions are padded to this
+constexpr int ROW_TILE = 64;     // rows per GEMM tile
+constexpr int REGION_ALIGN = 128; // the branch regions of the row space are padded to this (the largest row tile of any kernel)
 constexpr float LOG2E_F = 0x1.715476p+0f;
 constexpr float MASK_VALUE = -100.0f;
 constexpr float RND_MAGIC = 12582912.0f;          // 1.5 * 2^23: adding it rounds to an integer, ties to even
@@ -135,15 +136,15 @@ __device__ __forceinline__ int mfma_row(int r, int g) { return (r >> 2) * 8 + g 
 
 // Geometry of one forward call.  Rows of the gathered activation matrices: the
 // high group of all images first (slot = b*k_hi + j), padded to a multiple of
-// ROW_TILE, then the low group (slot = b*k_lo + j - k_hi).
+// REGION_ALIGN, then the low group (slot = b*k_lo + j - k_hi).
 struct Geom {
     int B, H, W, C, shift, heads;
     int Hp, Wp, nWc, nW;
     int k_hi, k_lo;              // windows per image in the high / low branch (the rest is pruned)
     int n_slots;                 // B*(k_hi+k_lo) windows that are computed
     int rows_hi, rows_lo;        // valid rows per region (B*k*49)
-    int base_lo;                 // first row of the low region (multiple of ROW_TILE)
-    int rows_total;              // multiple of ROW_TILE
+    int base_lo;                 // first row of the low region (multiple of REGION_ALIGN)
+    int rows_total;              // multiple of REGION_ALIGN
 };
 
 // row -> branch, canonical slot-major row (g*49+t) and source pixel index (or -1)
