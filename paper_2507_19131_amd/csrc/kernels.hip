@@ -289,7 +289,9 @@ __device__ __forceinline__ void epilogue(const GemmArgs& A, const Geom& G, int b
     }
 }
 
-constexpr int GEMM_RING = 4;          // operand slabs in flight per wave in the long-K GEMM
+constexpr int GEMM_RING = 4;          // operand slabs in flight per wave in the long-K GEMM (6 and 8 measured: no faster)
+constexpr int GEMM_SPLITK_MIN_K = 2048; // ... and only from this K (below, one wave's epilogue for four costs more than the shorter chain saves)
+constexpr int GEMM_SPLITK_TILES = 64; // up to this many 64-row tiles the long-K GEMM splits K over a workgroup's waves
 template <int KS, int EPI>      // KS = K/32 when the activation fragments fit in registers, 0 = stream them
 __global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
 {
@@ -359,6 +361,84 @@ __global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
         }
         epilogue<EPI>(A, G, branch, row0 + j, nb, g, c0, pix[0], canon[0], gelu_lds);
         epilogue<EPI>(A, G, branch, row0 + 32 + j, nb, g, c1, pix[1], canon[1], gelu_lds);
+    }
+}
+
+// Long K on few rows (the widest stage at batch 1: 20 row tiles): every wave's serial chain of slab loads, not
+// the matrix cores, sets the time, so the four waves of a workgroup share ONE 64-row tile and ONE output block
+// and split K between them; the partial sums meet in LDS and wave 0 runs the epilogue.  K/32 a multiple of 4.
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_splitk_kernel(Geom G, GemmArgs A)
+{
+    constexpr int D = 6;                                              // slabs in flight per wave
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 31, g = lane >> 5;
+    __shared__ v4i part[3][8][64];                                    // partial sums of waves 1..3: 32 ints per lane
+    __shared__ float4 gtab[EPI == EPI_FC1 ? GELU_K : 1];
+    if (EPI == EPI_FC1) gelu_stage_table(gtab, A.gelu_tab, threadIdx.x, 256);   // visible after the first barrier below
+    const float4* gelu_lds = gtab;
+    const int row0 = blockIdx.x * ROW_TILE;
+    const int branch = row0 >= G.base_lo ? 1 : 0;
+    const int K = A.K, ks_n = K / 32, per = ks_n / 4, k_lo = wave * per, NB = A.N / 32;
+    const int nb_lo = blockIdx.y * A.nb_per_block, nb_hi = min(nb_lo + A.nb_per_block, NB);
+    const int8_t* a0p = A.A + (size_t)(row0 + j) * K + g * 16 + k_lo * 32;
+    const int8_t* a1p = a0p + (size_t)32 * K;
+    int pix[2] = {0, 0}, canon[2] = {-1, -1};
+    if (wave == 0) {
+        canon[0] = A.row_canon[row0 + j]; canon[1] = A.row_canon[row0 + 32 + j];
+        if (EPI == EPI_PROJ || EPI == EPI_FC2) { pix[0] = A.row_pix[row0 + j]; pix[1] = A.row_pix[row0 + 32 + j]; }
+    }
+    for (int nb = nb_lo; nb < nb_hi; ++nb) {
+        v16i c0 = {0}, c1;
+        if (wave == 0) {   // accumulators start at -zp_in * colsum(W[n,:])
+            const int* nc = A.negcorr[branch] + nb * 32 + g * 4;
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                int4 t = *(const int4*)(nc + qd * 8);
+                c0[qd * 4 + 0] = t.x; c0[qd * 4 + 1] = t.y; c0[qd * 4 + 2] = t.z; c0[qd * 4 + 3] = t.w;
+            }
+        }
+        c1 = c0;
+        const v4i* wp = A.Wp + ((size_t)nb * ks_n + k_lo) * 64 + lane;
+        v4i rw[D], r0[D], r1[D];
+#pragma unroll
+        for (int d = 0; d < D; ++d) {                                    // fewer than D slabs: the last one again (unused)
+            const int ks = min(d, per - 1);
+            rw[d] = wp[ks * 64]; r0[d] = *(const v4i*)(a0p + ks * 32); r1[d] = *(const v4i*)(a1p + ks * 32);
+        }
+#pragma unroll 1
+        for (int k0 = 0; k0 < per; k0 += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                const v4i w = rw[d], x0 = r0[d], x1 = r1[d];
+                const int ks = min(k0 + D + d, per - 1);                 // past the end: the last slab again (unused)
+                rw[d] = wp[ks * 64]; r0[d] = *(const v4i*)(a0p + ks * 32); r1[d] = *(const v4i*)(a1p + ks * 32);
+                if (k0 + d < per) {                                      // wave-uniform: the last turn may be partial
+                    c0 = mfma32(w, x0, c0);
+                    c1 = mfma32(w, x1, c1);
+                }
+            }
+        }
+        if (wave > 0) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                part[wave - 1][q][lane] = (v4i){c0[4 * q], c0[4 * q + 1], c0[4 * q + 2], c0[4 * q + 3]};
+                part[wave - 1][4 + q][lane] = (v4i){c1[4 * q], c1[4 * q + 1], c1[4 * q + 2], c1[4 * q + 3]};
+            }
+        }
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int w = 0; w < 3; ++w)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const v4i p0 = part[w][q][lane], p1 = part[w][4 + q][lane];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { c0[4 * q + e] += p0[e]; c1[4 * q + e] += p1[e]; }
+                }
+            epilogue<EPI>(A, G, branch, row0 + j, nb, g, c0, pix[0], canon[0], gelu_lds);
+            epilogue<EPI>(A, G, branch, row0 + 32 + j, nb, g, c1, pix[1], canon[1], gelu_lds);
+        }
+        __syncthreads();                                              // the partial sums are free again
     }
 }
 
@@ -1595,6 +1675,14 @@ static void launch_gemm_e(const Geom& G, const GemmArgs& A0, hipStream_t st)
     int split = 1;                                   // split the channel blocks until the grid fills the chip
     while (gx * split < 1024 && split < NB) ++split;
     A.nb_per_block = (NB + split - 1) / split;
+    const bool long_k = A.K > 384;                  // the streaming form
+    if (long_k && A.K >= GEMM_SPLITK_MIN_K && (A.K / 32) % 4 == 0 && tiles <= GEMM_SPLITK_TILES) {     // few rows: split K over the waves of a workgroup
+        split = 1;
+        while (tiles * split < 1024 && split < NB) ++split;
+        A.nb_per_block = (NB + split - 1) / split;
+        hipLaunchKernelGGL((gemm_splitk_kernel<EPI>), dim3(tiles, (NB + A.nb_per_block - 1) / A.nb_per_block), dim3(256), 0, st, G, A);
+        return;
+    }
     dim3 grid(gx, (NB + A.nb_per_block - 1) / A.nb_per_block);
     switch (A.K) {
         case 96: hipLaunchKernelGGL((gemm_kernel<3, EPI>), grid, dim3(256), 0, st, G, A); break;
