@@ -449,24 +449,26 @@ __global__ __launch_bounds__(256) void gemm_splitk_kernel(Geom G, GemmArgs A)
 // of O^T = V^T P^T.  qf/kf: lane = token tb*32+j, 16 bytes = the lane half's 16 dims (any
 // mapping, the same for q and k).  vt: lane = dim j, byte r of slab kb = V[kb*32 +
 // mfma_row(r,g)][j], zero for keys >= 49.  Returns the raw P.V sums (lane = query, register
-// r = dim mfma_row(r,g)).
+// r = dim mfma_row(r,g)).  The wave runs NIB query blocks starting at block ib0 (both, or one of the
+// two when a pair of waves shares the head).
 struct AttnCore {
     const PolyCoef* poly;
-    const float* bm;          // [49 keys][64 queries] (bias + mask) * log2e of this head and mask type
+    const float* bq;          // (bias + mask) * log2e of query j of query block ib0 at key g*4, in the [49 keys][64 queries]
+                              // table of this head and mask type: key k + g*4, query block ib0 + ib is bq[k * 64 + ib * 32]
     float m2;
     QDev qp;
     int32_t* tap_s;           // already offset to this (slot, head): [49][49]
     int8_t* tap_p;
 };
 
-template <bool TAPS>
-__device__ __forceinline__ void attention_core(const v4i (&qf)[2], const v4i (&kf)[2], const v4i (&vt)[2],
-                                               const AttnCore& A, int j, int g, v16i (&o)[2])
+template <bool TAPS, int NIB>
+__device__ __forceinline__ void attention_core(const v4i (&qf)[NIB], const v4i (&kf)[2], const v4i (&vt)[2],
+                                               const AttnCore& A, int j, int g, int ib0, v16i (&o)[NIB])
 {
     const v16i zero16 = {0};
 #pragma unroll
-    for (int ib = 0; ib < 2; ++ib) {
-        const int qi = ib * 32 + j;                                       // this lane's query
+    for (int ib = 0; ib < NIB; ++ib) {
+        const int qi = (ib0 + ib) * 32 + j;                               // this lane's query
         v16i s[2];                                                        // S^T tiles of this query block, per key block
         s[0] = mfma32(kf[0], qf[ib], zero16);
         s[1] = mfma32(kf[1], qf[ib], zero16);
@@ -480,7 +482,7 @@ __device__ __forceinline__ void attention_core(const v4i (&qf)[2], const v4i (&k
                 float v = -INFINITY;
                 if (key < TOK) {                                          // valid for at least one half
                     const int kk = key + g * 4;
-                    if (kk < TOK) v = fmaf((float)s[kb][r], A.m2, A.bm[kk * 64 + qi]);
+                    if (kk < TOK) v = fmaf((float)s[kb][r], A.m2, A.bq[key * 64 + ib * 32]);
                     mx = fmaxf(mx, v);
                     if (TAPS && kk < TOK && qi < TOK && A.tap_s) A.tap_s[qi * TOK + kk] = s[kb][r];
                 }
@@ -531,23 +533,25 @@ __device__ __forceinline__ void attention_core(const v4i (&qf)[2], const v4i (&k
 }
 
 // zero-point correction, dequantization and requantization of the P.V sums; writes the codes
-// of head `head` for the window's tokens to out[row0 + token][C] (and the taps).
-template <bool TAPS>
-__device__ __forceinline__ void attention_store(const v16i (&o)[2], const int* csum, const QDev& qp, const QDev& qo, float m_o,
-                                                int j, int g, int head, int C, int8_t* out, int row0, int32_t* tap_o,
+// of head `head` for the window's tokens to out[row0 + token][C] (and the taps).  zcsum[d] = zp * sum of
+// the V codes of dim d over the keys, formed once per dim by the caller (an integer multiply is a
+// quarter-rate instruction; inside the loop it would be one per output element).
+template <bool TAPS, int NIB>
+__device__ __forceinline__ void attention_store(const v16i (&o)[NIB], const int* zcsum, const QDev& qo, float m_o,
+                                                int j, int g, int ib0, int head, int C, int8_t* out, int row0, int32_t* tap_o,
                                                 int8_t* tap_code, size_t canon_row0, int pack = 0)
 {
 #pragma unroll
-    for (int ib = 0; ib < 2; ++ib) {
-        const int qi = ib * 32 + j;
+    for (int ib = 0; ib < NIB; ++ib) {
+        const int qi = (ib0 + ib) * 32 + j;
         if (qi < TOK) {
             int code[4];
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 const int d0 = qd * 8 + g * 4;
-                const int4 cz = *(const int4*)(csum + d0);
-                int a0 = o[ib][qd * 4 + 0] - qp.zp * cz.x, a1 = o[ib][qd * 4 + 1] - qp.zp * cz.y;
-                int a2 = o[ib][qd * 4 + 2] - qp.zp * cz.z, a3 = o[ib][qd * 4 + 3] - qp.zp * cz.w;
+                const int4 cz = *(const int4*)(zcsum + d0);
+                int a0 = o[ib][qd * 4 + 0] - cz.x, a1 = o[ib][qd * 4 + 1] - cz.y;
+                int a2 = o[ib][qd * 4 + 2] - cz.z, a3 = o[ib][qd * 4 + 3] - cz.w;
                 code[qd] = pack4(quant_code((float)a0 * m_o, qo), quant_code((float)a1 * m_o, qo),
                                  quant_code((float)a2 * m_o, qo), quant_code((float)a3 * m_o, qo));
                 const int ch = head * HD + d0;
@@ -632,59 +636,66 @@ __global__ __launch_bounds__(256) void attn_kernel(Geom G, AttnArgs A)
         vt[kb] = (v4i){wd[0], wd[1], wd[2], wd[3]};
     }
     cs += __shfl_xor(cs, 32, 64);
-    if (g == 0) csum[wave][j] = cs;
+    if (g == 0) csum[wave][j] = A.qp[branch].zp * cs;
     AttnCore core;
     core.poly = &A.poly;
-    core.bm = A.bias2 + ((size_t)(mtype * G.heads + head) * TOK) * 64;
+    core.bq = A.bias2 + ((size_t)(mtype * G.heads + head) * TOK) * 64 + g * 4 * 64 + j;
     core.m2 = A.m2[branch];
     core.qp = A.qp[branch];
     const size_t tb = ((size_t)canon_slot * G.heads + head) * TOK * TOK;
     core.tap_s = A.tap_s ? A.tap_s + tb : nullptr;
     core.tap_p = A.tap_p ? A.tap_p + tb : nullptr;
     v16i o[2];
-    attention_core<true>(qf, kf, vt, core, j, g, o);
+    attention_core<true, 2>(qf, kf, vt, core, j, g, 0, o);
     __builtin_amdgcn_s_waitcnt(0);
     __builtin_amdgcn_wave_barrier();
-    attention_store<true>(o, csum[wave], core.qp, A.qo[branch], A.m_o[branch], j, g, head, G.C, A.out, row0, A.tap_o, A.tap_code,
+    attention_store<true, 2>(o, csum[wave], A.qo[branch], A.m_o[branch], j, g, 0, head, G.C, A.out, row0, A.tap_o, A.tap_code,
                     (size_t)canon_slot * TOK);
 }
 
 // ------------------------------------------------------------------ fused window kernel
 // One workgroup per window slot (HG = 1) or per half of a window's heads (HG = 2: few windows, or more heads
-// than a workgroup has waves; both halves repeat the gather + LN1 phase), one wave per head (NH waves):
+// than a workgroup has waves; both halves repeat the gather + LN1 phase), one wave per head (QS = 1, NH waves)
+// or a pair of waves per head (QS = 2: each wave projects one 32-token block to q, k and v, the pair exchanges
+// k and v through LDS, and each runs the attention of its own query block: half the chain of dependent steps):
 //   gather (shift folded into the index map) + LN1 + quantize, shared through LDS as MFMA
 //   fragments -> per head: q, k (transposed product, lane = token) and v (plain product, lane =
 //   dim) straight into operand registers -> attention core -> codes of the attention output.
 constexpr int WIN_WAVES_PER_EU = 3;
-template <int NH, int HG>
+template <int NH, int HG, int QS>
 struct WinCfg {
-    // lanes per token in the LN phase: one per wave (3, 4, 6, 8 or 12), so that the 49 tokens fit one pass
+    // lanes per token in the LN phase: one per wave (3 ... 16), so that the 49 tokens fit one pass
     // with about three quarters of the lanes busy; a wave holds 64/LPT whole groups
-    static constexpr int LPT = NH;
+    static constexpr int LPT = NH * QS;
     static constexpr int GPW = 64 / LPT;                             // groups (tokens) per wave
-    static constexpr int NV = NH * HG * 32 / (4 * LPT);              // float4 per lane = 8 * HG
+    static constexpr int NV = NH * HG * 32 / (4 * LPT);              // float4 per lane = 8 * HG / QS
 };
+constexpr int win_waves_per_eu(int NH, int HG, int QS) { return QS == 2 ? 4 : (HG == 2 && NH <= 8) ? 2 : WIN_WAVES_PER_EU; }
 
 // word offsets inside the window kernel's parameter block of one branch (see WinArgs::params)
 template <int C> struct WinPrm {
     static constexpr int LN_G = 0, LN_B = C, M = 2 * C, B = 5 * C, NC = 8 * C, WORDS = 11 * C;
 };
 
-template <int NH, bool TAPS, bool SCORED, int HG = 1>
-__global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 2 && NH <= 8) ? 2 : WIN_WAVES_PER_EU))) void window_kernel(Geom G, WinArgs A)
+template <int NH, bool TAPS, bool SCORED, int HG = 1, int QS = 1>
+__global__ __launch_bounds__(NH * QS * 64) __attribute__((amdgpu_waves_per_eu(win_waves_per_eu(NH, HG, QS)))) void window_kernel(Geom G, WinArgs A)
 {
     constexpr int NHT = NH * HG;                                         // heads of the block; this workgroup runs NH of them
-    constexpr int C = NHT * 32, KS = NHT, LPT = WinCfg<NH, HG>::LPT, NV = WinCfg<NH, HG>::NV, NT = NH * 64;
-    constexpr int GPW = WinCfg<NH, HG>::GPW;
+    constexpr int NW = NH * QS, NTB = 2 / QS;                            // waves; token blocks a wave projects and attends for
+    constexpr int C = NHT * 32, KS = NHT, LPT = WinCfg<NH, HG, QS>::LPT, NV = WinCfg<NH, HG, QS>::NV, NT = NW * 64;
+    constexpr int GPW = WinCfg<NH, HG, QS>::GPW;
     using PR = WinPrm<C>;
     const int widx = HG == 1 ? blockIdx.x : blockIdx.x / HG, hg = HG == 1 ? 0 : blockIdx.x % HG;
-    static_assert(NH * GPW >= TOK, "one pass must cover the window");
+    static_assert(NW * GPW >= TOK, "one pass must cover the window");
     __shared__ v4i a1s[2 * KS * 64];                                     // LN1 codes as fragments [token block][k slab][lane]
     __shared__ __attribute__((aligned(16))) float prm[PR::WORDS];        // this branch's LN1 affine and QKV epilogue constants
-    __shared__ __attribute__((aligned(16))) int csum[NH][HD];
-    __shared__ int red[NH];
+    __shared__ __attribute__((aligned(16))) int csum[NW][HD];
+    __shared__ v4i kvx[QS == 2 ? NH * 4 * 64 : 1];                       // k and v operands of a wave pair [head][k|v][token block][lane]
+    __shared__ int csp[QS == 2 ? NH * 2 * HD : 1];                       // V column sums of each token block [head][block][dim]
+    __shared__ int red[NW];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, g = lane >> 5;
-    const int head = hg * NH + wave;
+    const int hw = QS == 1 ? wave : wave >> 1, tb0 = QS == 1 ? 0 : wave & 1;   // head inside the workgroup, first token block
+    const int head = hg * NH + hw;
     constexpr bool HOIST = KS <= 8;
     constexpr int RING = 6;
     auto weights_of = [&](int which) { return A.Wqkv + (size_t)(which * NHT + head) * KS * 64 + lane; };
@@ -759,7 +770,7 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
         __syncthreads();
         int rank = 0;
 #pragma unroll
-        for (int k = 0; k < NH; ++k) rank += red[k];
+        for (int k = 0; k < NW; ++k) rank += red[k];
         if (tid == 0 && hg == 0) A.perm_out[(size_t)bimg * G.nW + rank] = w;
         if (rank >= G.k_hi + G.k_lo) {                                    // pruned (Sec. 3.4): forward the features
             if (pix >= 0 && hg == 0) {
@@ -806,12 +817,12 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
     // Operand handling.  Up to eight heads the LN1 fragments of both token blocks and the weight
     // fragments of one output block sit in registers; beyond that the B operand is read from LDS
     // inside the chain and the weight fragments stream through a short ring.
-    v4i bf[2][HOIST ? KS : 1];
+    v4i bf[NTB][HOIST ? KS : 1];
     if (HOIST) {
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
+        for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) bf[tb][ks] = a1s[(tb * KS + ks) * 64 + lane];
+            for (int ks = 0; ks < KS; ++ks) bf[tb][ks] = a1s[((tb0 + tb) * KS + ks) * 64 + lane];
     }
     // streaming form: acc[tb] += (weights as A operand ? W * act^T : act * W^T) over the whole K
     auto chain = [&](const v4i* wp, v16i* acc, bool weights_first) {
@@ -822,13 +833,15 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
         for (int ks = 0; ks < KS; ++ks) {
             const v4i wv = ring[ks % RING];
             if (ks + RING < KS) ring[ks % RING] = wp[(ks + RING) * 64];
-            const v4i x0 = a1s[ks * 64 + lane], x1 = a1s[(KS + ks) * 64 + lane];
-            acc[0] = weights_first ? mfma32(wv, x0, acc[0]) : mfma32(x0, wv, acc[0]);
-            acc[1] = weights_first ? mfma32(wv, x1, acc[1]) : mfma32(x1, wv, acc[1]);
+#pragma unroll
+            for (int tb = 0; tb < NTB; ++tb) {
+                const v4i xv = a1s[((tb0 + tb) * KS + ks) * 64 + lane];
+                acc[tb] = weights_first ? mfma32(wv, xv, acc[tb]) : mfma32(xv, wv, acc[tb]);
+            }
         }
     };
     const size_t canon_row0 = (size_t)canon_slot * TOK;
-    v4i qk[2][2];                                                        // [q|k][token block]
+    v4i qk[2][NTB];                                                      // [q|k][token block]
 #pragma unroll
     for (int which = 0; which < 2; ++which) {
         const int nb = which * NHT + head;
@@ -843,7 +856,7 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
         };
         auto finish = [&](int tb, const v16i& acc) {                      // dequantize, requantize, keep as operand
             int wd[4];
-            const int tok = tb * 32 + j;
+            const int tok = (tb0 + tb) * 32 + j;
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 const int n0 = nb * 32 + qd * 8 + g * 4;
@@ -863,7 +876,7 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) wf[ks] = wp[ks * 64];
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb) {
+            for (int tb = 0; tb < NTB; ++tb) {
                 v16i acc;
                 start(acc);
 #pragma unroll
@@ -871,12 +884,12 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
                 finish(tb, acc);
             }
         } else {
-            v16i acc[2];
+            v16i acc[NTB];
             start(acc[0]);
-            acc[1] = acc[0];
+            if (NTB == 2) acc[NTB - 1] = acc[0];
             chain(wp, acc, true);
-            finish(0, acc[0]);
-            finish(1, acc[1]);
+#pragma unroll
+            for (int tb = 0; tb < NTB; ++tb) finish(tb, acc[tb]);
         }
     }
     v4i vt[2];
@@ -894,9 +907,9 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
                 int c[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const int tok = tb * 32 + qd * 8 + g * 4 + e;
+                    const int tok = (tb0 + tb) * 32 + qd * 8 + g * 4 + e;
                     c[e] = 0;
-                    if (tb * 32 + qd * 8 + e < TOK) {
+                    if (QS == 2 || tb * 32 + qd * 8 + e < TOK) {      // known at compile time when the wave runs both blocks
                         if (tok < TOK) {
                             c[e] = quant_code(fmaf((float)acc[qd * 4 + e], m, bs), qv);
                             if (TAPS && A.tap_acc) A.tap_acc[(canon_row0 + tok) * (3 * C) + n] = acc[qd * 4 + e];
@@ -914,7 +927,7 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) wf[ks] = wp[ks * 64];
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb) {
+            for (int tb = 0; tb < NTB; ++tb) {
                 v16i acc;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[r] = nc;
@@ -923,33 +936,47 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu((HG == 
                 finish(tb, acc);
             }
         } else {
-            v16i acc[2];
+            v16i acc[NTB];
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[0][r] = nc;
-            acc[1] = acc[0];
+            if (NTB == 2) acc[NTB - 1] = acc[0];
             chain(wp, acc, false);
-            finish(0, acc[0]);
-            finish(1, acc[1]);
+#pragma unroll
+            for (int tb = 0; tb < NTB; ++tb) finish(tb, acc[tb]);
         }
         cs += __shfl_xor(cs, 32, 64);
-        if (g == 0) csum[wave][j] = cs;
+        if (QS == 1) {
+            if (g == 0) csum[wave][j] = A.qp[branch].zp * cs;
+        } else {                                                          // the pair exchanges its halves of K, V and the sums
+            kvx[((hw * 2 + 0) * 2 + tb0) * 64 + lane] = qk[1][0];
+            kvx[((hw * 2 + 1) * 2 + tb0) * 64 + lane] = vt[0];
+            if (g == 0) csp[(hw * 2 + tb0) * HD + j] = cs;
+            __syncthreads();
+            if (g == 0) csum[wave][j] = A.qp[branch].zp * (csp[(hw * 2) * HD + j] + csp[(hw * 2 + 1) * HD + j]);
+        }
+    }
+    v4i kf[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        kf[kb] = QS == 1 ? qk[1][kb % NTB] : kvx[((hw * 2 + 0) * 2 + kb) * 64 + lane];
+        if (QS == 2) vt[kb] = kvx[((hw * 2 + 1) * 2 + kb) * 64 + lane];
     }
     AttnCore core;
     core.poly = &A.poly;
-    core.bm = A.bias2 + ((size_t)(mask_type(G, w) * NHT + head) * TOK) * 64;
+    core.bq = A.bias2 + ((size_t)(mask_type(G, w) * NHT + head) * TOK) * 64 + g * 4 * 64 + tb0 * 32 + j;
     core.m2 = A.m2[branch];
     core.qp = A.qp[branch];
     const size_t tbase = ((size_t)canon_slot * NHT + head) * TOK * TOK;
     core.tap_s = A.tap_s ? A.tap_s + tbase : nullptr;
     core.tap_p = A.tap_p ? A.tap_p + tbase : nullptr;
-    v16i o[2];
-    attention_core<TAPS>(qk[0], qk[1], vt, core, j, g, o);
+    v16i o[NTB];
+    attention_core<TAPS, NTB>(qk[0], kf, vt, core, j, g, tb0, o);
     __builtin_amdgcn_s_waitcnt(0);
     __builtin_amdgcn_wave_barrier();
     const int pack = branch ? A.out_pack : 0;                            // the low region's rows may be packed (dense, after the high region)
-    if (pack) attention_store<TAPS>(o, csum[wave], core.qp, A.qo[branch], A.m_o[branch], j, g, head, C, A.out + (size_t)G.base_lo * C,
-                                    row0 - G.base_lo, A.tap_o, A.tap_code, canon_row0, pack);
-    else attention_store<TAPS>(o, csum[wave], core.qp, A.qo[branch], A.m_o[branch], j, g, head, C, A.out, row0, A.tap_o, A.tap_code, canon_row0);
+    if (pack) attention_store<TAPS, NTB>(o, csum[wave], A.qo[branch], A.m_o[branch], j, g, tb0, head, C, A.out + (size_t)G.base_lo * C,
+                                         row0 - G.base_lo, A.tap_o, A.tap_code, canon_row0, pack);
+    else attention_store<TAPS, NTB>(o, csum[wave], A.qo[branch], A.m_o[branch], j, g, tb0, head, C, A.out, row0, A.tap_o, A.tap_code, canon_row0);
 }
 
 // ------------------------------------------------------------------ fused token kernel
@@ -1711,32 +1738,44 @@ bool fused_window_supported(int C) { return C == 96 || C == 128 || C == 192 || C
 bool fused_token_supported(int C, int mlp_ratio) { return (C == 96 || C == 128 || C == 192 || C == 256 || C == 384) && mlp_ratio == 4; }
 
 constexpr int WINDOW_SPLIT_SMALL = 128;      // C = 384: up to this many windows, two workgroups share a window's heads
+// Up to this many windows a pair of waves shares a head.  The pair form has the shorter chain of dependent steps
+// (a workgroup alone on its CU: 9.5 instead of 11.2 us at C = 96) but 15 % more vector and 80 % more scalar
+// instructions per window, so it loses once the CUs are full (1392 windows at C = 96: 31 instead of 28.3 us;
+// 5476 at C = 128: 113 instead of 101 us).  At C = 192 it wins on 360 windows (22.8 instead of 25.4 us); at
+// C = 256 it measures the same on 1444 windows and is not instantiated.
+constexpr int WINDOW_PAIR_SMALL = 256, WINDOW_PAIR_SMALL_6 = 512;
 void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
 {
     // every window gets a workgroup: with scores it finds its own rank (and may turn out pruned), otherwise
     // the computed slots come first and the pruned windows of the list after them
     const int n_wg = G.B * G.nW;
     if (n_wg == 0) return;
-#define WIN_CASE(NH, HG)                                                                                               \
-    {                                                                                                                  \
-        const dim3 grid(n_wg * HG);                                                                                    \
-        if (A.scores) {                                                                                                \
-            if (A.taps) hipLaunchKernelGGL((window_kernel<NH, true, true, HG>), grid, dim3(NH * 64), 0, st, G, A);     \
-            else hipLaunchKernelGGL((window_kernel<NH, false, true, HG>), grid, dim3(NH * 64), 0, st, G, A);           \
-        } else {                                                                                                       \
-            if (A.taps) hipLaunchKernelGGL((window_kernel<NH, true, false, HG>), grid, dim3(NH * 64), 0, st, G, A);    \
-            else hipLaunchKernelGGL((window_kernel<NH, false, false, HG>), grid, dim3(NH * 64), 0, st, G, A);          \
-        }                                                                                                              \
-    }                                                                                                                  \
+#define WIN_CASE(NH, HG, QS)                                                                                              \
+    {                                                                                                                     \
+        const dim3 grid(n_wg * HG), block(NH * QS * 64);                                                                  \
+        if (A.scores) {                                                                                                   \
+            if (A.taps) hipLaunchKernelGGL((window_kernel<NH, true, true, HG, QS>), grid, block, 0, st, G, A);            \
+            else hipLaunchKernelGGL((window_kernel<NH, false, true, HG, QS>), grid, block, 0, st, G, A);                  \
+        } else {                                                                                                          \
+            if (A.taps) hipLaunchKernelGGL((window_kernel<NH, true, false, HG, QS>), grid, block, 0, st, G, A);           \
+            else hipLaunchKernelGGL((window_kernel<NH, false, false, HG, QS>), grid, block, 0, st, G, A);                 \
+        }                                                                                                                 \
+    }                                                                                                                     \
     break
     switch (G.C / 32) {
-        case 3: WIN_CASE(3, 1);
-        case 4: WIN_CASE(4, 1);
-        case 6: WIN_CASE(6, 1);
-        case 8: WIN_CASE(8, 1);
+        case 3:
+            if (n_wg <= WINDOW_PAIR_SMALL) { WIN_CASE(3, 1, 2); }
+            WIN_CASE(3, 1, 1);
+        case 4:
+            if (n_wg <= WINDOW_PAIR_SMALL) { WIN_CASE(4, 1, 2); }
+            WIN_CASE(4, 1, 1);
+        case 6:
+            if (n_wg <= WINDOW_PAIR_SMALL_6) { WIN_CASE(6, 1, 2); }
+            WIN_CASE(6, 1, 1);
+        case 8: WIN_CASE(8, 1, 1);
         case 12:
-            if (n_wg <= WINDOW_SPLIT_SMALL) { WIN_CASE(6, 2); }
-            WIN_CASE(12, 1);
+            if (n_wg <= WINDOW_SPLIT_SMALL) { WIN_CASE(6, 2, 1); }
+            WIN_CASE(12, 1, 1);
         default: break;
     }
 #undef WIN_CASE

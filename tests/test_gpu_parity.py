@@ -37,6 +37,7 @@ SMALL = [
     (1, 7, 7, 96, 3, 0, 1.0, 20, {}),                                                 # a single window
     (1, 5, 6, 96, 3, 0, 0.0, 24, {}),                                                 # a map smaller than one window
     (2, 3, 20, 128, 4, 0, 0.5, 25, {}),                                               # one row of windows, mostly padding
+    (3, 98, 98, 192, 6, 3, 0.5, 26, {}),                                              # 588 windows at six heads: one wave per head
 ]
 
 
