@@ -771,6 +771,7 @@ __global__ __launch_bounds__(NH * QS * 64) __attribute__((amdgpu_waves_per_eu(wi
         int rank = 0;
 #pragma unroll
         for (int k = 0; k < NW; ++k) rank += red[k];
+        rank = __builtin_amdgcn_readfirstlane(rank);                      // the same in every lane: what follows from it stays scalar
         if (tid == 0 && hg == 0) A.perm_out[(size_t)bimg * G.nW + rank] = w;
         if (rank >= G.k_hi + G.k_lo) {                                    // pruned (Sec. 3.4): forward the features
             if (pix >= 0 && hg == 0) {
