@@ -405,6 +405,24 @@ def main():
                 entry["chain"] = backbone_chain(M, synth, torch, 100)
             configs[name] = entry
 
+    # ---------------------------------------------------------------- config 2's shape at larger batches (context, not the headline)
+    # One 200x336 map gives every CU five or six windows per kernel, so each of the five kernels of a step runs
+    # mostly in its ramp-up and its tail; the same kernels on a batch show the rate they sustain once the chip is full.
+    batch_scaling = None
+    if not args.headline_only:
+        import dataclasses
+        batch_scaling = []
+        for b in (2, 4, 8):
+            st0 = wl["stages"][0]
+            wlb = dict(wl, stages=[dict(st0, spec=dataclasses.replace(st0["spec"], B=b))])
+            stg = Stage(M, synth, torch, wlb, 0, wl["keep"][0])
+            stg.spin_up(0.05)
+            ms = stg.time_steps(300, 50)
+            wps = stg.n_win * len(stg.blocks) / (ms * 1e-3)
+            batch_scaling.append(dict(B=b, ms_per_pass=round(ms, 5), windows_per_s=round(wps, 1),
+                                      int_tops=round(2 * macs_per_window(spec.C) * wps / 1e12, 2)))
+            stg.close()
+
     out = dict(metric="windows/sec & effective int-TOPS per two-branch Swin block; % int8 MFMA peak",
                value=round(value, 1), unit="windows/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=round(ms_per_step, 5), higher_is_better=True, scaling="weak", vs_baseline=None,
@@ -416,7 +434,8 @@ def main():
                                           value=round(windows_per_step / (ms_per_step_m1 * 1e-3), 1)),
                int_tops=round(int_tops, 3), pct_int8_mfma_peak=round(100 * int_tops / PEAK_INT8_TOPS, 3),
                ms_per_block=round(ms_per_step / 2, 5), frac_of_fused_ideal=round(value / ideal_windows_per_s(spec.C), 5),
-               roofline=roofline, kernels=kernels, cpu_baseline=cpu, configs=configs)
+               roofline=roofline, kernels=kernels, cpu_baseline=cpu, configs=configs,
+               cfg2_shape_at_larger_batches=batch_scaling)
     calibration_copy(torch, dev)
     print(json.dumps(out))
     return 0
