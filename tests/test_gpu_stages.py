@@ -54,6 +54,19 @@ def test_config2_stage_pair():
     check(*run_stage(st["spec"], st["shifts"], wl["keep"][0], wl["seed"], wl["blobs"], wl["outliers"], wl.get("ranges")))
 
 
+def test_config2_shape_on_a_batch_of_four():
+    """The benchmark's context entry: config 2's stage on four maps at once (5568 windows per block, the selection
+    taken per image)."""
+    import dataclasses
+    wl = synth.workload("cfg2")
+    st = wl["stages"][0]
+    spec = dataclasses.replace(st["spec"], B=4)
+    print("config 2 shape, batch 4", flush=True)
+    y_gpu, y_or, perm_gpu, perm_or = run_stage(spec, st["shifts"], wl["keep"][0], wl["seed"], wl["blobs"], wl["outliers"], wl.get("ranges"))
+    assert perm_gpu.shape == (4, spec.nW) and all(sorted(row) == list(range(spec.nW)) for row in perm_gpu.tolist())
+    check(y_gpu, y_or, perm_gpu, perm_or)
+
+
 @pytest.mark.parametrize("keep", [0.25, 0.5, 0.75])
 def test_config3_six_blocks(keep):
     wl = synth.workload("cfg3")
