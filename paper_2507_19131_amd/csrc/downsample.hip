@@ -5,6 +5,7 @@
 // they are here so that the four stages of a backbone run as one chain on the GPU.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -65,6 +66,105 @@ __device__ __forceinline__ float4 ds_values(const DsArgs& A, int b, int i, int j
     return v;
 }
 
+// Patch merging of the usual widths (C_in = 4 LPT NV4, LPT lanes per token, 4 NV4 = NV float4 per lane: C_in a
+// multiple of 48 or 64 up to 512).  One workgroup (4 waves) per 32 output tokens and per group of output blocks.
+// Phase 1: LPT lanes hold the 4 C_in inputs of a token in registers (NV independent 16-byte loads per lane, the
+// neighbour of each known at compile time), LayerNorm statistics in binary64 over the lane group, quantize, codes
+// to LDS as MFMA operand fragments; 256 / LPT tokens per pass.  Phase 2: wave w computes the output blocks
+// first + w, first + w + 4, ... of its group: the weight fragments stream through a ring of loads in flight.
+template <int LPT, int NV, bool TAPS>
+__global__ __launch_bounds__(256) void merge_kernel(DsArgs A, int blocks_per_group)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int TP = 256 / LPT, PER = NV / 4, KSN = NV * LPT / 8, RING = KSN % 8 == 0 ? 8 : 6;
+    static_assert(NV % 4 == 0 && (LPT & (LPT - 1)) == 0 && LPT <= 64 && KSN % RING == 0, "lane groups inside a wave, whole ring turns");
+    v4i* frag = (v4i*)smem;                                   // [KSN][64]
+    int* fragw = (int*)smem;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int grp = tid / LPT, sub = tid % LPT;
+#pragma unroll 1
+    for (int p0 = 0; p0 < 32; p0 += TP) {
+        const int jt = p0 + grp, tok = blockIdx.x * 32 + jt;
+        const bool valid = tok < A.tokens;
+        const int b = tok / (A.Ho * A.Wo), rem = tok - b * (A.Ho * A.Wo), i = rem / A.Wo, j = rem - i * A.Wo;
+        float4 v[NV];
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {                        // element k of the lane: neighbour k / PER, channels ((k % PER) LPT + sub) 4 ..
+            const int q = k / PER, r = 2 * i + (q & 1), c = 2 * j + (q >> 1);
+            v[k] = (valid && r < A.H && c < A.W)
+                       ? *(const float4*)(A.x + (((size_t)b * A.H + r) * A.W + c) * A.Cin + ((k % PER) * LPT + sub) * 4)
+                       : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        double s = 0.0;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) s += ((double)v[k].x + (double)v[k].y) + ((double)v[k].z + (double)v[k].w);
+#pragma unroll
+        for (int o = LPT / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+        const float mean = (float)(s / (double)A.K);
+        double qv = 0.0;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const double a0 = (double)v[k].x - (double)mean, a1 = (double)v[k].y - (double)mean;
+            const double a2 = (double)v[k].z - (double)mean, a3 = (double)v[k].w - (double)mean;
+            qv += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+        }
+#pragma unroll
+        for (int o = LPT / 2; o >= 1; o >>= 1) qv += __shfl_xor(qv, o, 64);
+        const float var = (float)(qv / (double)A.K);
+        const float rstd = 1.0f / sqrtf(var + A.eps);
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const int k0 = (k * LPT + sub) * 4;
+            int code = 0;
+            if (valid) {
+                const float4 gm = *(const float4*)(A.gamma + k0), bt = *(const float4*)(A.beta + k0);
+                code = pack4(quant_code(fmaf((v[k].x - mean) * rstd, gm.x, bt.x), A.q), quant_code(fmaf((v[k].y - mean) * rstd, gm.y, bt.y), A.q),
+                             quant_code(fmaf((v[k].z - mean) * rstd, gm.z, bt.z), A.q), quant_code(fmaf((v[k].w - mean) * rstd, gm.w, bt.w), A.q));
+                if (TAPS && A.tap_codes && blockIdx.y == 0) *(int*)(A.tap_codes + (size_t)tok * A.K + k0) = code;
+            }
+            fragw[(((k0 >> 5) * 64 + ((k0 & 31) >> 4) * 32 + jt) << 2) + ((k0 & 15) >> 2)] = code;
+        }
+    }
+    __syncthreads();
+    const int j = lane & 31, g = lane >> 5;
+    const int tok = blockIdx.x * 32 + j;
+    const bool valid = tok < A.tokens;
+    const int first = blockIdx.y * blocks_per_group, last = min(first + blocks_per_group, A.N / 32);
+    for (int nb = first + wave; nb < last; nb += 4) {
+        const v4i* wp = A.Wp + (size_t)nb * KSN * 64 + lane;
+        v4i ring[RING];
+#pragma unroll
+        for (int d = 0; d < RING; ++d) ring[d] = wp[d * 64];
+        v16i acc;
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            const int4 t4 = *(const int4*)(A.negcorr + nb * 32 + qd * 8 + g * 4);
+            acc[qd * 4 + 0] = t4.x; acc[qd * 4 + 1] = t4.y; acc[qd * 4 + 2] = t4.z; acc[qd * 4 + 3] = t4.w;
+        }
+#pragma unroll 1
+        for (int k0 = 0; k0 < KSN; k0 += RING) {
+#pragma unroll
+            for (int d = 0; d < RING; ++d) {
+                const v4i wv = ring[d];
+                ring[d] = wp[min(k0 + RING + d, KSN - 1) * 64];           // past the end: the last fragment again, unused
+                acc = mfma32(wv, frag[(k0 + d) * 64 + lane], acc);
+            }
+        }
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            const int n0 = nb * 32 + qd * 8 + g * 4;
+            const float4 m = *(const float4*)(A.m + n0), bs = *(const float4*)(A.bias + n0);
+            if (valid) {
+                *(float4*)(A.y + (size_t)tok * A.N + n0) =
+                    make_float4(fmaf((float)acc[qd * 4 + 0], m.x, bs.x), fmaf((float)acc[qd * 4 + 1], m.y, bs.y),
+                                fmaf((float)acc[qd * 4 + 2], m.z, bs.z), fmaf((float)acc[qd * 4 + 3], m.w, bs.w));
+                if (TAPS && A.tap_acc) *(int4*)(A.tap_acc + (size_t)tok * A.N + n0) = make_int4(acc[qd * 4], acc[qd * 4 + 1], acc[qd * 4 + 2], acc[qd * 4 + 3]);
+            }
+        }
+    }
+}
+
+// The general form (patch embedding; patch merging of other widths).
 // One workgroup (4 waves) per 32 output tokens.  Phase 1: eight lanes per token gather the K inputs
 // (kind 1: LayerNorm over them, binary64 sums), quantize, and lay the codes out in LDS as MFMA
 // operand fragments.  Phase 2: wave w computes the output blocks w, w+4, ...: W * codes^T, lane =
@@ -251,7 +351,29 @@ int ds_forward(const mixaq_downsample* h, const float* x, float* y, void* stream
     const dim3 grid((A.tokens + 31) / 32);
     const size_t lds = ds_lds_bytes(h);
     hipStream_t st = (hipStream_t)stream;
-    if (h->d.kind == 0) hipLaunchKernelGGL(downsample_kernel<0>, grid, dim3(256), lds, st, A);
+    // patch merging of the usual widths: lanes per token and registers per lane from C_in; the output blocks are split
+    // into groups of at least four (one per wave) over more workgroups while the grid has fewer than about 512
+    int lpt = 0, nv = 0;
+    if (h->d.kind == 1) {
+        for (int n : {12, 16})
+            for (int l : {8, 16, 32})
+                if (!lpt && A.Cin == n * l) { lpt = l; nv = n; }
+    }
+    if (lpt) {
+        const int NB = A.N / 32, tiles = (int)grid.x;
+        int groups = std::max(1, std::min(NB / 4, (512 + tiles - 1) / tiles));
+        const int per = ((NB + groups - 1) / groups + 3) / 4 * 4;
+        groups = (NB + per - 1) / per;
+        const dim3 grid2(tiles, groups);
+        const bool taps = tap_codes || tap_acc;
+#define MERGE_CASE(L, V)                                                                                          \
+    if (lpt == L && nv == V) {                                                                                    \
+        if (taps) hipLaunchKernelGGL((merge_kernel<L, V, true>), grid2, dim3(256), (size_t)A.Kp * 32, st, A, per);  \
+        else hipLaunchKernelGGL((merge_kernel<L, V, false>), grid2, dim3(256), (size_t)A.Kp * 32, st, A, per);     \
+    }
+        MERGE_CASE(8, 12) MERGE_CASE(16, 12) MERGE_CASE(32, 12) MERGE_CASE(8, 16) MERGE_CASE(16, 16) MERGE_CASE(32, 16)
+#undef MERGE_CASE
+    } else if (h->d.kind == 0) hipLaunchKernelGGL(downsample_kernel<0>, grid, dim3(256), lds, st, A);
     else hipLaunchKernelGGL(downsample_kernel<1>, grid, dim3(256), lds, st, A);
     HIP_TRY(hipGetLastError());
     return MIXAQ_OK;

@@ -41,7 +41,12 @@ CASES = [
     (0, 2, 50, 45, 3, 96, 4, 4),        # sizes that are not multiples of the patch
     (1, 1, 28, 42, 96, 192, 8, 8),
     (1, 2, 15, 21, 192, 384, 4, 4),     # odd sizes: zero padding before the LayerNorm
-    (1, 1, 14, 14, 384, 768, 6, 8),
+    (1, 1, 14, 14, 384, 768, 6, 8),     # few tokens: the output blocks are split over workgroups
+    (1, 1, 20, 26, 128, 256, 8, 8),     # Swin-B widths: sixteen vectors per lane
+    (1, 1, 13, 14, 256, 512, 8, 8),
+    (1, 1, 10, 12, 512, 1024, 8, 4),
+    (1, 2, 12, 10, 64, 128, 8, 8),      # a width outside the register-resident forms: the general kernel
+    (1, 1, 112, 150, 96, 192, 8, 8),    # many tokens: one group of output blocks
 ]
 
 
