@@ -44,11 +44,13 @@ __device__ __forceinline__ double sum8(double v)      // over the 8 lanes of a t
 }
 
 // the four input values k0..k0+3 of output token (b,i,j); zero outside the map and beyond K
-template <int KIND>
+// (PC, CC: patch size and input channels when known at compile time, so that the index divisions are by constants; 0 = from A)
+template <int KIND, int PC = 0, int CC = 0>
 __device__ __forceinline__ float4 ds_values(const DsArgs& A, int b, int i, int j, int k0)
 {
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     if (k0 >= A.K) return v;
+    const int P = PC ? PC : A.P, Cin = CC ? CC : A.Cin;
     if (KIND == 1) {                  // 2x2 neighbours in the order (0,0), (1,0), (0,1), (1,1) [row, column offset]
         const int q = k0 / A.Cin, ch = k0 - q * A.Cin;
         const int r = 2 * i + (q & 1), c = 2 * j + (q >> 1);
@@ -57,9 +59,9 @@ __device__ __forceinline__ float4 ds_values(const DsArgs& A, int b, int i, int j
         float e[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int k = k0 + t, pc = k / A.Cin, ch = k - pc * A.Cin, di = pc / A.P, dj = pc - di * A.P;
-            const int r = i * A.P + di, c = j * A.P + dj;
-            e[t] = (r < A.H && c < A.W) ? A.x[(((size_t)b * A.H + r) * A.W + c) * A.Cin + ch] : 0.f;
+            const int k = k0 + t, pc = k / Cin, ch = k - pc * Cin, di = pc / P, dj = pc - di * P;
+            const int r = i * P + di, c = j * P + dj;
+            e[t] = (r < A.H && c < A.W) ? A.x[(((size_t)b * A.H + r) * A.W + c) * Cin + ch] : 0.f;
         }
         v = make_float4(e[0], e[1], e[2], e[3]);
     }
@@ -170,7 +172,7 @@ __global__ __launch_bounds__(256) void merge_kernel(DsArgs A, int blocks_per_gro
 // operand fragments.  Phase 2: wave w computes the output blocks w, w+4, ...: W * codes^T, lane =
 // token, 16 channels per block; dequantize; kind 1 stores, kind 0 goes through LDS for the
 // LayerNorm over the N outputs of a token.
-template <int KIND>
+template <int KIND, int PC = 0, int CC = 0>
 __global__ __launch_bounds__(256) void downsample_kernel(DsArgs A)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -189,7 +191,7 @@ __global__ __launch_bounds__(256) void downsample_kernel(DsArgs A)
             double s = 0.0;
             if (valid)
                 for (int c4 = sub; c4 < nreal; c4 += 8) {
-                    const float4 v = ds_values<KIND>(A, b, i, j, c4 * 4);
+                    const float4 v = ds_values<KIND, PC, CC>(A, b, i, j, c4 * 4);
                     s += ((double)v.x + (double)v.y) + ((double)v.z + (double)v.w);
                 }
             s = sum8(s);
@@ -197,7 +199,7 @@ __global__ __launch_bounds__(256) void downsample_kernel(DsArgs A)
             double qv = 0.0;
             if (valid)
                 for (int c4 = sub; c4 < nreal; c4 += 8) {
-                    const float4 v = ds_values<KIND>(A, b, i, j, c4 * 4);
+                    const float4 v = ds_values<KIND, PC, CC>(A, b, i, j, c4 * 4);
                     const double a0 = (double)v.x - (double)mean, a1 = (double)v.y - (double)mean;
                     const double a2 = (double)v.z - (double)mean, a3 = (double)v.w - (double)mean;
                     qv += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
@@ -210,7 +212,7 @@ __global__ __launch_bounds__(256) void downsample_kernel(DsArgs A)
             const int k0 = c4 * 4;
             int code = 0;
             if (valid && k0 < A.K) {
-                float4 v = ds_values<KIND>(A, b, i, j, k0);
+                float4 v = ds_values<KIND, PC, CC>(A, b, i, j, k0);
                 if (KIND == 1) {
                     const float4 gm = *(const float4*)(A.gamma + k0), bt = *(const float4*)(A.beta + k0);
                     v.x = fmaf((v.x - mean) * rstd, gm.x, bt.x);
@@ -373,7 +375,8 @@ int ds_forward(const mixaq_downsample* h, const float* x, float* y, void* stream
     }
         MERGE_CASE(8, 12) MERGE_CASE(16, 12) MERGE_CASE(32, 12) MERGE_CASE(8, 16) MERGE_CASE(16, 16) MERGE_CASE(32, 16)
 #undef MERGE_CASE
-    } else if (h->d.kind == 0) hipLaunchKernelGGL(downsample_kernel<0>, grid, dim3(256), lds, st, A);
+    } else if (h->d.kind == 0 && A.P == 4 && A.Cin == 3) hipLaunchKernelGGL((downsample_kernel<0, 4, 3>), grid, dim3(256), lds, st, A);
+    else if (h->d.kind == 0) hipLaunchKernelGGL(downsample_kernel<0>, grid, dim3(256), lds, st, A);
     else hipLaunchKernelGGL(downsample_kernel<1>, grid, dim3(256), lds, st, A);
     HIP_TRY(hipGetLastError());
     return MIXAQ_OK;

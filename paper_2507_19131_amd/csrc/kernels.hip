@@ -6,6 +6,7 @@
 //   attn_kernel       per (window, head): QK^T, bias+mask, softmax, P.V
 // Arithmetic that decides an integer code follows the pinned binary32 sequences
 // of mixaq_dev.h; reductions feeding a code run in binary64.
+#include <algorithm>
 #include "mixaq_dev.h"
 #include "kernels.h"
 
@@ -361,6 +362,82 @@ __global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
         }
         epilogue<EPI>(A, G, branch, row0 + j, nb, g, c0, pix[0], canon[0], gelu_lds);
         epilogue<EPI>(A, G, branch, row0 + 32 + j, nb, g, c1, pix[1], canon[1], gelu_lds);
+    }
+}
+
+// Few rows (the widest stages at batch 1: 20 row tiles at C = 768): one workgroup per 64-row tile and group of
+// output blocks.  The tile's activation rows are read once, 16 contiguous bytes per lane, and laid out in LDS as
+// MFMA operand fragments (the row-major codes read directly as operands are 16 bytes from each of 32 rows per
+// load, a quarter of every cache line touched); wave w computes the output blocks first + w, first + w + 4, ...
+// of the group: weight fragments stream through a ring of loads in flight, the B operand comes from LDS.
+constexpr int GEMM_TILE_MAX_TILES = 256;   // up to this many row tiles (above, the chip is full without the split over output blocks)
+constexpr int GEMM_TILE_MAX_K = 2048;      // 64 rows x K bytes of LDS
+template <int EPI, int KMAX>      // KMAX: bytes of K the instantiation's LDS holds per row; a longer K goes through in chunks of KMAX
+__global__ __launch_bounds__(256) void gemm_tile_kernel(Geom G, GemmArgs A)
+{
+    __shared__ v4i afr[ROW_TILE * KMAX / 16];                          // [2 row blocks][chunk slabs][64 lanes]
+    __shared__ float4 gtab[EPI == EPI_FC1 ? GELU_K : 1];
+    constexpr int D = 8;                                               // weight fragments in flight per wave
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, g = lane >> 5;
+    const int row0 = blockIdx.x * ROW_TILE;
+    const int branch = row0 >= G.base_lo ? 1 : 0;
+    const int K = A.K, ks_n = K / 32, NB = A.N / 32;
+    const int kch = min(K, KMAX), cs = kch / 32, n_ch = K / kch, per_row = kch / 16;   // chunk bytes, slabs per chunk, chunks
+    auto stage = [&](int ch) {     // piece (row r, 16-byte chunk q) -> fragment (r/32, q/2), lane (r%32, q%2)
+        for (int p = tid; p < ROW_TILE * per_row; p += 256) {
+            const int r = p / per_row, q = p - r * per_row;
+            afr[((r >> 5) * cs + (q >> 1)) * 64 + (q & 1) * 32 + (r & 31)] = *(const v4i*)(A.A + (size_t)(row0 + r) * K + ch * kch + q * 16);
+        }
+    };
+    if (EPI == EPI_FC1) gelu_stage_table(gtab, A.gelu_tab, tid, 256);
+    const float4* gelu_lds = gtab;
+    int pix[2] = {0, 0}, canon[2];
+    canon[0] = A.row_canon[row0 + j]; canon[1] = A.row_canon[row0 + 32 + j];
+    if (EPI == EPI_PROJ || EPI == EPI_FC2) { pix[0] = A.row_pix[row0 + j]; pix[1] = A.row_pix[row0 + 32 + j]; }
+    if (n_ch == 1) stage(0);                                           // the whole K stays for every output block
+    __syncthreads();
+    const int nb_lo = blockIdx.y * A.nb_per_block, nb_hi = min(nb_lo + A.nb_per_block, NB);
+    for (int nb0 = nb_lo; nb0 < nb_hi; nb0 += 4) {                     // the same trips for every wave: barriers inside
+        const int nb = min(nb0 + wave, NB - 1);
+        const bool active = nb0 + wave < nb_hi;
+        const v4i* wp = A.Wp + (size_t)nb * ks_n * 64 + lane;
+        v4i rw[D];
+#pragma unroll
+        for (int d = 0; d < D; ++d) rw[d] = wp[min(d, ks_n - 1) * 64];  // K may hold fewer than D slabs: the last one again (unused)
+        v16i c0, c1;
+        {   // accumulators start at -zp_in * colsum(W[n,:])
+            const int* nc = A.negcorr[branch] + nb * 32 + g * 4;
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                int4 t = *(const int4*)(nc + qd * 8);
+                c0[qd * 4 + 0] = t.x; c0[qd * 4 + 1] = t.y; c0[qd * 4 + 2] = t.z; c0[qd * 4 + 3] = t.w;
+            }
+            c1 = c0;
+        }
+#pragma unroll 1
+        for (int ch = 0; ch < n_ch; ++ch) {
+            if (n_ch > 1) {
+                if (ch > 0 || nb0 > nb_lo) __syncthreads();             // the previous chunk is no longer read
+                stage(ch);
+                __syncthreads();
+            }
+#pragma unroll 1
+            for (int k0 = 0; k0 < cs; k0 += D) {
+#pragma unroll
+                for (int d = 0; d < D; ++d) {
+                    const v4i w = rw[d];
+                    rw[d] = wp[min(ch * cs + k0 + D + d, ks_n - 1) * 64]; // past the end: the last slab again (unused)
+                    if (k0 + d < cs) {                                   // wave-uniform: the last turn may be partial
+                        c0 = mfma32(w, afr[(k0 + d) * 64 + lane], c0);
+                        c1 = mfma32(w, afr[(cs + k0 + d) * 64 + lane], c1);
+                    }
+                }
+            }
+        }
+        if (active) {
+            epilogue<EPI>(A, G, branch, row0 + j, nb, g, c0, pix[0], canon[0], gelu_lds);
+            epilogue<EPI>(A, G, branch, row0 + 32 + j, nb, g, c1, pix[1], canon[1], gelu_lds);
+        }
     }
 }
 
@@ -1704,11 +1781,22 @@ static void launch_gemm_e(const Geom& G, const GemmArgs& A0, hipStream_t st)
     while (gx * split < 1024 && split < NB) ++split;
     A.nb_per_block = (NB + split - 1) / split;
     const bool long_k = A.K > 384;                  // the streaming form
+    const bool tile_form = tiles <= GEMM_TILE_MAX_TILES && (A.K <= GEMM_TILE_MAX_K || A.K % 1024 == 0);
     if (long_k && A.K >= GEMM_SPLITK_MIN_K && (A.K / 32) % 4 == 0 && tiles <= GEMM_SPLITK_TILES) {     // few rows: split K over the waves of a workgroup
         split = 1;
         while (tiles * split < 1024 && split < NB) ++split;
         A.nb_per_block = (NB + split - 1) / split;
         hipLaunchKernelGGL((gemm_splitk_kernel<EPI>), dim3(tiles, (NB + A.nb_per_block - 1) / A.nb_per_block), dim3(256), 0, st, G, A);
+        return;
+    }
+    if (tile_form) {                                 // few rows: activations through LDS, output blocks over the waves (K above 2048 in
+                                                     // chunks of 1024; where the K split above applies it measures faster: 22.7 against 27.8 us at K = 3072)
+        int groups = std::max(1, std::min((NB + 3) / 4, (512 + tiles - 1) / tiles));
+        A.nb_per_block = ((NB + groups - 1) / groups + 3) / 4 * 4;
+        const dim3 grid(tiles, (NB + A.nb_per_block - 1) / A.nb_per_block);
+        if (A.K <= 384) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 384>), grid, dim3(256), 0, st, G, A);
+        else if (A.K <= 1024 || A.K > GEMM_TILE_MAX_K) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 1024>), grid, dim3(256), 0, st, G, A);
+        else hipLaunchKernelGGL((gemm_tile_kernel<EPI, GEMM_TILE_MAX_K>), grid, dim3(256), 0, st, G, A);
         return;
     }
     dim3 grid(gx, (NB + A.nb_per_block - 1) / A.nb_per_block);

@@ -83,6 +83,17 @@ def test_other_mlp_ratios(C, heads, mlp_ratio):
     gh.assert_parity(res)
 
 
+def test_long_k_on_a_few_hundred_row_tiles():
+    """FC2 with K = 3072 on 111 row tiles: too many for the split of K over a workgroup's waves, so the GEMM that
+    stages the activation tile in LDS takes K in chunks."""
+    spec, inp, x, k = _case(2, 50, 60, 384, 12, 3, 0.5, 54, blobs=True, mlp_ratio=8)
+    assert spec.B * spec.nW * 49 > 64 * 64
+    print("long K, chunked", flush=True)
+    res = gh.compare_block(inp, x, k)
+    print(res, flush=True)
+    gh.assert_parity(res)
+
+
 @pytest.mark.parametrize("fused", [True, False])
 @pytest.mark.parametrize("score_mode,value", [(0, float("nan")), (1, float("inf"))])
 def test_window_whose_score_is_not_a_number(score_mode, value, fused):
