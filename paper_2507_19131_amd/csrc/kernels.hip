@@ -1271,216 +1271,6 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(tok_wav
     }
 }
 
-// ------------------------------------------------------------------ fused token kernel, streaming form
-// For the wider stages (C >= 192), where re-reading all 12 C^2 weight bytes per 32 rows would bind on
-// L2 bandwidth.  One workgroup per tile of 64 gathered rows (two 32-row blocks share every weight
-// fragment), one wave per 32-channel block.  The K = C operands (attention codes, then LN2 codes) are
-// staged once in LDS as fragments; weight fragments stream from L2 through a ring of RING loads in
-// flight; the FFN is cut into four chunks of NH hidden blocks: FC1 + GELU + quantize of a chunk goes to
-// one of two LDS buffers, then FC2 accumulates that chunk, so the hidden activations never exist as
-// a whole.  Epilogue constants are read from the per-branch parameter block in global memory.
-constexpr int token_ring(int NH) { return NH == 8 ? 8 : NH == 12 ? 12 : 6; }   // weight fragments in flight per wave
-template <int NH, bool TAPS, int RB>   // RB = 32-row blocks per tile (2; 1 when the map has too few rows to fill the chip)
-__global__ __launch_bounds__(NH * 64) void token_stream_kernel(Geom G, TokArgs A)
-{
-    constexpr int C = NH * 32, KS = NH, HB = 4 * NH, F = 4 * C, NT = NH * 64, RING = token_ring(NH);
-    static_assert(NH % RING == 0, "a chain is a whole number of ring turns");
-    using PR = TokPrm<C>;
-    __shared__ v4i actf[RB * KS * 64];                                 // [row block][k slab][lane]
-    __shared__ v4i gs[2][NH * RB * 64];                                // [buffer][hidden block of the chunk][row block][lane]
-    __shared__ double part[2][NH][32 * RB];
-    __shared__ float4 gtab[GELU_K];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, g = lane >> 5;
-    const int tile = blockIdx.x, row_base = tile * (32 * RB);
-    const int branch = row_base >= G.base_lo ? 1 : 0;                 // a tile never straddles the regions: scalar
-    const int nb = wave;
-    const float* prm = A.params[branch];
-    const int* prmi = (const int*)prm;
-    int pix[RB];
-    bool valid[RB];
-    size_t canon[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const int row = row_base + rb * 32 + j;
-        valid[rb] = branch ? (row - G.base_lo < G.rows_lo) : (row < G.rows_hi);
-        pix[rb] = valid[rb] ? A.row_pix[row] : -1;
-        canon[rb] = (TAPS && valid[rb]) ? (size_t)A.row_canon[row] : 0;
-    }
-    // stage the attention codes of the tile: piece p = (row r, 16-byte chunk q) -> fragment (r/32, q/2), lane (r%32, q%2)
-    const int pack = branch ? A.ao_pack : 0;                           // packed low-branch codes: scalar per tile
-    for (int p = tid; p < 32 * RB * (C / 16); p += NT) {
-        const int r = p / (C / 16), q = p - r * (C / 16);
-        actf[((r >> 5) * KS + (q >> 1)) * 64 + (q & 1) * 32 + (r & 31)] =
-            pack ? unpack_codes(A.ao + (size_t)G.base_lo * C + (size_t)(row_base - G.base_lo + r) * (C >> pack), pack, q >> 1, q & 1)
-                 : *(const v4i*)(A.ao + (size_t)(row_base + r) * C + q * 16);
-    }
-    gelu_stage_table(gtab, A.gelu_tab, tid, NT);
-    // acc[rb] += W(fragments wp[0], wp[64], ...) * operand fragments b[(rb * stride_rb + i) * 64 + lane]
-    auto start = [&](v16i* acc, int off) {                             // accumulators start at -zp * colsum
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd) {
-            const int4 t4 = *(const int4*)(prmi + off + qd * 8 + g * 4);
-            acc[0][qd * 4 + 0] = t4.x; acc[0][qd * 4 + 1] = t4.y; acc[0][qd * 4 + 2] = t4.z; acc[0][qd * 4 + 3] = t4.w;
-        }
-        if (RB == 2) acc[RB - 1] = acc[0];
-    };
-    v4i ring[RING];
-    auto request = [&](const v4i* wp) {
-#pragma unroll
-        for (int d = 0; d < RING; ++d) ring[d] = wp[d * 64];
-    };
-    // acc[rb] += W * operand^T over n fragments: weights from the ring (refilled n fragments ahead
-    // from wp), operand fragment i of row block rb at b[(rb * rb_stride + i * i_stride) * 64 + lane]
-    auto chain = [&](const v4i* wp, const v4i* b, int rb_stride, int i_stride, int n, v16i* acc) {
-#pragma unroll 1
-        for (int i0 = 0; i0 < n; i0 += RING) {
-#pragma unroll
-            for (int d = 0; d < RING; ++d) {
-                const int i = i0 + d;
-                const v4i wv = ring[d];
-                if (i + RING < n) ring[d] = wp[(i + RING) * 64];
-                acc[0] = mfma32(wv, b[(i * i_stride) * 64 + lane], acc[0]);
-                if (RB == 2) acc[RB - 1] = mfma32(wv, b[(rb_stride + i * i_stride) * 64 + lane], acc[RB - 1]);
-            }
-        }
-    };
-    __syncthreads();                                                  // staged codes and table visible
-    float h[RB][16];
-    {   // output projection + first residual
-        const v4i* wp = A.Wproj + (size_t)nb * KS * 64 + lane;
-        request(wp);
-        float4 sc[RB][4];                                              // shortcut of the first residual, in flight during the chain
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-            for (int qd = 0; qd < 4; ++qd)
-                sc[rb][qd] = pix[rb] >= 0 ? *(const float4*)(A.x + (size_t)pix[rb] * C + nb * 32 + qd * 8 + g * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-        v16i acc[RB];
-        start(acc, PR::P_NC + nb * 32);
-        chain(wp, actf, KS, 1, KS, acc);
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                const int n0 = nb * 32 + qd * 8 + g * 4;
-                const float4 m = *(const float4*)(prm + PR::P_M + n0), bs = *(const float4*)(prm + PR::P_B + n0);
-                h[rb][qd * 4 + 0] = fmaf((float)acc[rb][qd * 4 + 0], m.x, bs.x) + sc[rb][qd].x;
-                h[rb][qd * 4 + 1] = fmaf((float)acc[rb][qd * 4 + 1], m.y, bs.y) + sc[rb][qd].y;
-                h[rb][qd * 4 + 2] = fmaf((float)acc[rb][qd * 4 + 2], m.z, bs.z) + sc[rb][qd].z;
-                h[rb][qd * 4 + 3] = fmaf((float)acc[rb][qd * 4 + 3], m.w, bs.w) + sc[rb][qd].w;
-                if (TAPS && valid[rb]) {
-                    if (A.tap_acc_proj) *(int4*)(A.tap_acc_proj + canon[rb] * C + n0) = make_int4(acc[rb][qd * 4], acc[rb][qd * 4 + 1], acc[rb][qd * 4 + 2], acc[rb][qd * 4 + 3]);
-                    if (A.tap_h) *(float4*)(A.tap_h + canon[rb] * C + n0) = make_float4(h[rb][qd * 4], h[rb][qd * 4 + 1], h[rb][qd * 4 + 2], h[rb][qd * 4 + 3]);
-                }
-            }
-    }
-    request(A.W1 + (size_t)wave * KS * 64 + lane);                    // first FC1 chain, in flight during LN2
-    {   // LN2: binary64 partial sums per (wave, token) through LDS, then normalise and quantize
-        float mean[RB], rstd[RB];
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            double s = 0.0;
-#pragma unroll
-            for (int r = 0; r < 16; r += 4) s += ((double)h[rb][r] + (double)h[rb][r + 1]) + ((double)h[rb][r + 2] + (double)h[rb][r + 3]);
-            s += __shfl_xor(s, 32, 64);
-            if (g == 0) part[0][wave][rb * 32 + j] = s;
-        }
-        __syncthreads();                                              // also: every wave is done reading the attention codes
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            double tot = 0.0;
-#pragma unroll
-            for (int w2 = 0; w2 < NH; ++w2) tot += part[0][w2][rb * 32 + j];
-            mean[rb] = (float)(tot / (double)C);
-            double q = 0.0;
-#pragma unroll
-            for (int r = 0; r < 16; r += 4) {
-                double a = (double)h[rb][r] - (double)mean[rb], b = (double)h[rb][r + 1] - (double)mean[rb];
-                double c = (double)h[rb][r + 2] - (double)mean[rb], d = (double)h[rb][r + 3] - (double)mean[rb];
-                q += (a * a + b * b) + (c * c + d * d);
-            }
-            q += __shfl_xor(q, 32, 64);
-            if (g == 0) part[1][wave][rb * 32 + j] = q;
-        }
-        __syncthreads();
-        const QDev qa = A.q_fc1in[branch];
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            double tot = 0.0;
-#pragma unroll
-            for (int w2 = 0; w2 < NH; ++w2) tot += part[1][w2][rb * 32 + j];
-            const float var = (float)(tot / (double)C);
-            rstd[rb] = 1.0f / sqrtf(var + A.eps);
-            int wd[4];
-#pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                const int n0 = nb * 32 + qd * 8 + g * 4;
-                const float4 gm = *(const float4*)(prm + PR::LN_G + n0), bt = *(const float4*)(prm + PR::LN_B + n0);
-                wd[qd] = pack4(quant_code(fmaf((h[rb][qd * 4 + 0] - mean[rb]) * rstd[rb], gm.x, bt.x), qa),
-                               quant_code(fmaf((h[rb][qd * 4 + 1] - mean[rb]) * rstd[rb], gm.y, bt.y), qa),
-                               quant_code(fmaf((h[rb][qd * 4 + 2] - mean[rb]) * rstd[rb], gm.z, bt.z), qa),
-                               quant_code(fmaf((h[rb][qd * 4 + 3] - mean[rb]) * rstd[rb], gm.w, bt.w), qa));
-                if (TAPS && valid[rb] && A.tap_a2) *(int*)(A.tap_a2 + canon[rb] * C + n0) = wd[qd];
-            }
-            actf[(rb * KS + nb) * 64 + lane] = (v4i){wd[0], wd[1], wd[2], wd[3]};   // k slab nb, byte r = channel 32nb + mfma_row(r,g)
-        }
-    }
-    __syncthreads();
-    v16i acc2[RB];
-    start(acc2, PR::F2_NC + nb * 32);
-    const QDev qg = A.q_fc2in[branch];
-#pragma unroll 1
-    for (int ch = 0; ch < 4; ++ch) {
-        const int hb = ch * NH + wave;
-        {   // FC1 + GELU + quantize of hidden block hb
-            const v4i* wp = A.W1 + (size_t)hb * KS * 64 + lane;
-            v16i acc[RB];
-            start(acc, PR::F1_NC + hb * 32);
-            chain(wp, actf, KS, 1, KS, acc);
-            request(A.W2 + ((size_t)nb * HB + ch * NH) * 64 + lane); // FC2 fragments of this chunk, in flight during the epilogue
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                int wd[4];
-#pragma unroll
-                for (int qd = 0; qd < 4; ++qd) {
-                    const int n0 = hb * 32 + qd * 8 + g * 4;
-                    const float4 m = *(const float4*)(prm + PR::F1_M + n0), bs = *(const float4*)(prm + PR::F1_B + n0);
-                    wd[qd] = pack4(quant_code(gelu_scaled(fmaf((float)acc[rb][qd * 4 + 0], m.x, bs.x), gtab), qg),
-                                   quant_code(gelu_scaled(fmaf((float)acc[rb][qd * 4 + 1], m.y, bs.y), gtab), qg),
-                                   quant_code(gelu_scaled(fmaf((float)acc[rb][qd * 4 + 2], m.z, bs.z), gtab), qg),
-                                   quant_code(gelu_scaled(fmaf((float)acc[rb][qd * 4 + 3], m.w, bs.w), gtab), qg));
-                    if (TAPS && valid[rb]) {
-                        if (A.tap_acc_fc1) *(int4*)(A.tap_acc_fc1 + canon[rb] * F + n0) = make_int4(acc[rb][qd * 4], acc[rb][qd * 4 + 1], acc[rb][qd * 4 + 2], acc[rb][qd * 4 + 3]);
-                        if (A.tap_g) *(int*)(A.tap_g + canon[rb] * F + n0) = wd[qd];
-                    }
-                }
-                gs[ch & 1][(wave * RB + rb) * 64 + lane] = (v4i){wd[0], wd[1], wd[2], wd[3]};
-            }
-        }
-        __syncthreads();                                              // chunk ch of the hidden codes complete
-        {   // FC2 over the chunk's NH hidden blocks
-            const v4i* wp = A.W2 + ((size_t)nb * HB + ch * NH) * 64 + lane;
-            const v4i* gb = gs[ch & 1];
-            chain(wp, gb, 1, RB, NH, acc2);
-            if (ch < 3) request(A.W1 + (size_t)(hb + NH) * KS * 64 + lane);
-        }
-    }
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd) {   // second residual + scatter
-            const int n0 = nb * 32 + qd * 8 + g * 4;
-            const float4 m = *(const float4*)(prm + PR::F2_M + n0), bs = *(const float4*)(prm + PR::F2_B + n0);
-            float4 o4 = make_float4(fmaf((float)acc2[rb][qd * 4 + 0], m.x, bs.x) + h[rb][qd * 4 + 0], fmaf((float)acc2[rb][qd * 4 + 1], m.y, bs.y) + h[rb][qd * 4 + 1],
-                                    fmaf((float)acc2[rb][qd * 4 + 2], m.z, bs.z) + h[rb][qd * 4 + 2], fmaf((float)acc2[rb][qd * 4 + 3], m.w, bs.w) + h[rb][qd * 4 + 3]);
-            if (pix[rb] >= 0) *(float4*)(A.y + (size_t)pix[rb] * C + n0) = o4;
-            if (TAPS && valid[rb]) {
-                if (A.tap_acc_fc2) *(int4*)(A.tap_acc_fc2 + canon[rb] * C + n0) = make_int4(acc2[rb][qd * 4], acc2[rb][qd * 4 + 1], acc2[rb][qd * 4 + 2], acc2[rb][qd * 4 + 3]);
-                if (A.tap_y) *(float4*)(A.tap_y + canon[rb] * C + n0) = o4;
-            }
-        }
-}
-
 // ------------------------------------------------------------------ fused token kernel, wide form
 // For the wide stages: one workgroup per tile of 32*RB gathered rows (RB 32-row blocks share every weight fragment,
 // which divides the L2 -> CU weight traffic per row by RB: each wave streams weights nobody else uses, so bytes
@@ -1870,8 +1660,7 @@ void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
 #undef WIN_CASE
 }
 
-constexpr int TOKEN_STREAM_SMALL = 128;
-constexpr int TOKEN_STREAM_FROM = 12;        // NH from which the streaming 64-row form is used (measured: the 32-row form wins below)
+constexpr int TOKEN_WIDE_SMALL = 128;        // C = 384: up to this many 64-row tiles the wide token kernel runs on 32-row tiles
 void launch_token(const Geom& G, const TokArgs& A, hipStream_t st)
 {
     if (G.rows_total == 0) return;
@@ -1880,13 +1669,13 @@ void launch_token(const Geom& G, const TokArgs& A, hipStream_t st)
     if (A.taps) hipLaunchKernelGGL((token_kernel<NH, true>), dim3(G.rows_total / 32), dim3(NH * 64), 0, st, G, A); \
     else hipLaunchKernelGGL((token_kernel<NH, false>), dim3(G.rows_total / 32), dim3(NH * 64), 0, st, G, A);      \
     break
-    // twelve heads: the wide 64-row form once there are enough tiles to give every second CU one, else 32-row tiles
-    if (NHr == 12 && G.rows_total / 64 > TOKEN_STREAM_SMALL) {
+    // twelve heads: the wide form, 64-row tiles once there are enough of them to give every second CU one, else 32-row tiles
+    if (NHr == 12 && G.rows_total / 64 > TOKEN_WIDE_SMALL) {
         if (A.taps) hipLaunchKernelGGL((token_wide_kernel<12, 2, true>), dim3(G.rows_total / 64), dim3(12 * 64), 0, st, G, A);
         else hipLaunchKernelGGL((token_wide_kernel<12, 2, false>), dim3(G.rows_total / 64), dim3(12 * 64), 0, st, G, A);
-    } else if (NHr >= TOKEN_STREAM_FROM) {
-        if (A.taps) hipLaunchKernelGGL((token_stream_kernel<12, true, 1>), dim3(G.rows_total / 32), dim3(12 * 64), 0, st, G, A);
-        else hipLaunchKernelGGL((token_stream_kernel<12, false, 1>), dim3(G.rows_total / 32), dim3(12 * 64), 0, st, G, A);
+    } else if (NHr == 12) {
+        if (A.taps) hipLaunchKernelGGL((token_wide_kernel<12, 1, true>), dim3(G.rows_total / 32), dim3(12 * 64), 0, st, G, A);
+        else hipLaunchKernelGGL((token_wide_kernel<12, 1, false>), dim3(G.rows_total / 32), dim3(12 * 64), 0, st, G, A);
     } else {
         switch (NHr) {
             case 3: TOK_CASE(3);
