@@ -1058,17 +1058,18 @@ __global__ __launch_bounds__(NH * QS * 64) __attribute__((amdgpu_waves_per_eu(wi
 }
 
 // ------------------------------------------------------------------ fused token kernel
-// One workgroup per tile of 32 gathered rows, one wave per 32-channel block (NH = C/32 waves):
+// One workgroup per tile of 32 gathered rows, one wave per 32-channel block (NH = C/32 = 3, 4 or 8 waves; six and
+// twelve waves run the wide form below):
 //   proj + first residual (wave w owns channels 32w..32w+31, h stays in registers) -> LN2 with
 //   statistics exchanged through LDS -> quantize -> FC1 (each wave 4 hidden blocks) + GELU +
 //   quantize, codes to LDS as fragments -> FC2 + second residual -> scatter to the map.
 // Latency is hidden by issuing loads a phase ahead: the per-branch parameter block (epilogue
 // constants, LN2 affine) is staged in LDS once, weight fragments of the next MFMA chain are
 // requested before the current epilogue starts.
-// waves per SIMD the token kernel is compiled for: two workgroups per CU with six or eight waves each (12 or 16
-// waves), four and five with four and three waves; measured: one more resident workgroup at eight waves takes the
-// kernel from 122 to 96 us on 70756 rows, five waves per SIMD at three or six waves per workgroup gain nothing
-constexpr int tok_waves_per_eu(int NH) { return NH == 6 ? 3 : 4; }
+// waves per SIMD the token kernel is compiled for: two workgroups per CU with eight waves each, four and five with
+// four and three waves; measured: one more resident workgroup at eight waves takes the kernel from 122 to 96 us
+// on 70756 rows, five waves per SIMD at three waves per workgroup gain nothing
+constexpr int tok_waves_per_eu(int) { return 4; }
 // word offsets inside the parameter block of one branch (see TokArgs::params)
 template <int C> struct TokPrm {
     static constexpr int F = 4 * C;
@@ -1083,7 +1084,7 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(tok_wav
     using PR = TokPrm<C>;
     constexpr int PV = PR::WORDS / 4, PVT = (PV + NT - 1) / NT;       // float4 of the block, per thread
     constexpr int D2 = 4;                                            // FC2 weight fragments in flight
-    constexpr bool EARLY_W1 = NH <= 6;                               // first FC1 weights requested at entry (register room permitting)
+    constexpr bool EARLY_W1 = NH <= 4;                               // first FC1 weights requested at entry (register room permitting)
     __shared__ v4i a2s[KS * 64];
     __shared__ v4i gs[HB * 64];
     __shared__ double part[2][NH][32];
@@ -1272,10 +1273,9 @@ __global__ __launch_bounds__(NH * 64) __attribute__((amdgpu_waves_per_eu(tok_wav
 }
 
 // ------------------------------------------------------------------ fused token kernel, wide form
-// For the wide stages: one workgroup per tile of 32*RB gathered rows (RB 32-row blocks share every weight fragment,
-// which divides the L2 -> CU weight traffic per row by RB: each wave streams weights nobody else uses, so bytes
-// in flight per CU, not bandwidth, bound that stream), one wave per 32-channel block.  Built for a small register
-// footprint: the per-branch parameter block sits in LDS, the weight fragments of the whole kernel form ONE stream
+// For six and twelve waves (C = 192, 384): one workgroup per tile of 32*RB gathered rows (RB 32-row blocks share
+// every weight fragment, which divides the L2 -> CU weight traffic per row by RB), one wave per 32-channel block.
+// Built for a small register footprint: the per-branch parameter block sits in LDS, the weight fragments of the whole kernel form ONE stream
 // per wave (projection block, then per chunk the FC1 block and the FC2 fragments) that is requested RING
 // fragments ahead across every phase boundary, and with twelve waves h is parked in the output map between the
 // first and the second residual (the same thread writes and re-reads the same address) instead of in registers.
@@ -1676,11 +1676,13 @@ void launch_token(const Geom& G, const TokArgs& A, hipStream_t st)
     } else if (NHr == 12) {
         if (A.taps) hipLaunchKernelGGL((token_wide_kernel<12, 1, true>), dim3(G.rows_total / 32), dim3(12 * 64), 0, st, G, A);
         else hipLaunchKernelGGL((token_wide_kernel<12, 1, false>), dim3(G.rows_total / 32), dim3(12 * 64), 0, st, G, A);
+    } else if (NHr == 6) {    // six waves: the wide form on 32-row tiles (28.9 instead of 32.3 us on 552 tiles; at 3, 4 and 8 waves the plain kernel wins)
+        if (A.taps) hipLaunchKernelGGL((token_wide_kernel<6, 1, true>), dim3(G.rows_total / 32), dim3(6 * 64), 0, st, G, A);
+        else hipLaunchKernelGGL((token_wide_kernel<6, 1, false>), dim3(G.rows_total / 32), dim3(6 * 64), 0, st, G, A);
     } else {
         switch (NHr) {
             case 3: TOK_CASE(3);
             case 4: TOK_CASE(4);
-            case 6: TOK_CASE(6);
             default: TOK_CASE(8);
         }
     }
