@@ -291,8 +291,6 @@ __device__ __forceinline__ void epilogue(const GemmArgs& A, const Geom& G, int b
 }
 
 constexpr int GEMM_RING = 4;          // operand slabs in flight per wave in the long-K GEMM (6 and 8 measured: no faster)
-constexpr int GEMM_SPLITK_MIN_K = 2048; // ... and only from this K (below, one wave's epilogue for four costs more than the shorter chain saves)
-constexpr int GEMM_SPLITK_TILES = 64; // up to this many 64-row tiles the long-K GEMM splits K over a workgroup's waves
 template <int KS, int EPI>      // KS = K/32 when the activation fragments fit in registers, 0 = stream them
 __global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
 {
@@ -370,30 +368,37 @@ __global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
 // MFMA operand fragments (the row-major codes read directly as operands are 16 bytes from each of 32 rows per
 // load, a quarter of every cache line touched); wave w computes the output blocks first + w, first + w + 4, ...
 // of the group: weight fragments stream through a ring of loads in flight, the B operand comes from LDS.
+// K up to 2048 stays whole in LDS for a 64-row tile, K up to 4096 for a 32-row tile; longer K passes in chunks.
 constexpr int GEMM_TILE_MAX_TILES = 256;   // up to this many row tiles (above, the chip is full without the split over output blocks)
 constexpr int GEMM_TILE_MAX_K = 2048;      // 64 rows x K bytes of LDS
-template <int EPI, int KMAX>      // KMAX: bytes of K the instantiation's LDS holds per row; a longer K goes through in chunks of KMAX
+// KMAX: bytes of K the instantiation's LDS holds per row (a longer K goes through in chunks of KMAX); RT: rows per tile,
+// 64 or, so that a long K fits LDS whole, 32
+template <int EPI, int KMAX, int RT = ROW_TILE>
 __global__ __launch_bounds__(256) void gemm_tile_kernel(Geom G, GemmArgs A)
 {
-    __shared__ v4i afr[ROW_TILE * KMAX / 16];                          // [2 row blocks][chunk slabs][64 lanes]
+    constexpr int RB = RT / 32;
+    __shared__ v4i afr[RT * KMAX / 16];                                // [row blocks][chunk slabs][64 lanes]
     __shared__ float4 gtab[EPI == EPI_FC1 ? GELU_K : 1];
     constexpr int D = 8;                                               // weight fragments in flight per wave
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, g = lane >> 5;
-    const int row0 = blockIdx.x * ROW_TILE;
+    const int row0 = blockIdx.x * RT;
     const int branch = row0 >= G.base_lo ? 1 : 0;
     const int K = A.K, ks_n = K / 32, NB = A.N / 32;
     const int kch = min(K, KMAX), cs = kch / 32, n_ch = K / kch, per_row = kch / 16;   // chunk bytes, slabs per chunk, chunks
     auto stage = [&](int ch) {     // piece (row r, 16-byte chunk q) -> fragment (r/32, q/2), lane (r%32, q%2)
-        for (int p = tid; p < ROW_TILE * per_row; p += 256) {
+        for (int p = tid; p < RT * per_row; p += 256) {
             const int r = p / per_row, q = p - r * per_row;
             afr[((r >> 5) * cs + (q >> 1)) * 64 + (q & 1) * 32 + (r & 31)] = *(const v4i*)(A.A + (size_t)(row0 + r) * K + ch * kch + q * 16);
         }
     };
     if (EPI == EPI_FC1) gelu_stage_table(gtab, A.gelu_tab, tid, 256);
     const float4* gelu_lds = gtab;
-    int pix[2] = {0, 0}, canon[2];
-    canon[0] = A.row_canon[row0 + j]; canon[1] = A.row_canon[row0 + 32 + j];
-    if (EPI == EPI_PROJ || EPI == EPI_FC2) { pix[0] = A.row_pix[row0 + j]; pix[1] = A.row_pix[row0 + 32 + j]; }
+    int pix[RB], canon[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        canon[rb] = A.row_canon[row0 + rb * 32 + j];
+        pix[rb] = (EPI == EPI_PROJ || EPI == EPI_FC2) ? A.row_pix[row0 + rb * 32 + j] : 0;
+    }
     if (n_ch == 1) stage(0);                                           // the whole K stays for every output block
     __syncthreads();
     const int nb_lo = blockIdx.y * A.nb_per_block, nb_hi = min(nb_lo + A.nb_per_block, NB);
@@ -404,7 +409,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(Geom G, GemmArgs A)
         v4i rw[D];
 #pragma unroll
         for (int d = 0; d < D; ++d) rw[d] = wp[min(d, ks_n - 1) * 64];  // K may hold fewer than D slabs: the last one again (unused)
-        v16i c0, c1;
+        v16i c0, c1;                                                     // c1: the second row block (RT = 64)
         {   // accumulators start at -zp_in * colsum(W[n,:])
             const int* nc = A.negcorr[branch] + nb * 32 + g * 4;
 #pragma unroll
@@ -429,93 +434,15 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(Geom G, GemmArgs A)
                     rw[d] = wp[min(ch * cs + k0 + D + d, ks_n - 1) * 64]; // past the end: the last slab again (unused)
                     if (k0 + d < cs) {                                   // wave-uniform: the last turn may be partial
                         c0 = mfma32(w, afr[(k0 + d) * 64 + lane], c0);
-                        c1 = mfma32(w, afr[(cs + k0 + d) * 64 + lane], c1);
+                        if (RB == 2) c1 = mfma32(w, afr[(cs + k0 + d) * 64 + lane], c1);
                     }
                 }
             }
         }
         if (active) {
             epilogue<EPI>(A, G, branch, row0 + j, nb, g, c0, pix[0], canon[0], gelu_lds);
-            epilogue<EPI>(A, G, branch, row0 + 32 + j, nb, g, c1, pix[1], canon[1], gelu_lds);
+            if (RB == 2) epilogue<EPI>(A, G, branch, row0 + 32 + j, nb, g, c1, pix[RB - 1], canon[RB - 1], gelu_lds);
         }
-    }
-}
-
-// Long K on few rows (the widest stage at batch 1: 20 row tiles): every wave's serial chain of slab loads, not
-// the matrix cores, sets the time, so the four waves of a workgroup share ONE 64-row tile and ONE output block
-// and split K between them; the partial sums meet in LDS and wave 0 runs the epilogue.  K/32 a multiple of 4.
-template <int EPI>
-__global__ __launch_bounds__(256) void gemm_splitk_kernel(Geom G, GemmArgs A)
-{
-    constexpr int D = 6;                                              // slabs in flight per wave
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 31, g = lane >> 5;
-    __shared__ v4i part[3][8][64];                                    // partial sums of waves 1..3: 32 ints per lane
-    __shared__ float4 gtab[EPI == EPI_FC1 ? GELU_K : 1];
-    if (EPI == EPI_FC1) gelu_stage_table(gtab, A.gelu_tab, threadIdx.x, 256);   // visible after the first barrier below
-    const float4* gelu_lds = gtab;
-    const int row0 = blockIdx.x * ROW_TILE;
-    const int branch = row0 >= G.base_lo ? 1 : 0;
-    const int K = A.K, ks_n = K / 32, per = ks_n / 4, k_lo = wave * per, NB = A.N / 32;
-    const int nb_lo = blockIdx.y * A.nb_per_block, nb_hi = min(nb_lo + A.nb_per_block, NB);
-    const int8_t* a0p = A.A + (size_t)(row0 + j) * K + g * 16 + k_lo * 32;
-    const int8_t* a1p = a0p + (size_t)32 * K;
-    int pix[2] = {0, 0}, canon[2] = {-1, -1};
-    if (wave == 0) {
-        canon[0] = A.row_canon[row0 + j]; canon[1] = A.row_canon[row0 + 32 + j];
-        if (EPI == EPI_PROJ || EPI == EPI_FC2) { pix[0] = A.row_pix[row0 + j]; pix[1] = A.row_pix[row0 + 32 + j]; }
-    }
-    for (int nb = nb_lo; nb < nb_hi; ++nb) {
-        v16i c0 = {0}, c1;
-        if (wave == 0) {   // accumulators start at -zp_in * colsum(W[n,:])
-            const int* nc = A.negcorr[branch] + nb * 32 + g * 4;
-#pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                int4 t = *(const int4*)(nc + qd * 8);
-                c0[qd * 4 + 0] = t.x; c0[qd * 4 + 1] = t.y; c0[qd * 4 + 2] = t.z; c0[qd * 4 + 3] = t.w;
-            }
-        }
-        c1 = c0;
-        const v4i* wp = A.Wp + ((size_t)nb * ks_n + k_lo) * 64 + lane;
-        v4i rw[D], r0[D], r1[D];
-#pragma unroll
-        for (int d = 0; d < D; ++d) {                                    // fewer than D slabs: the last one again (unused)
-            const int ks = min(d, per - 1);
-            rw[d] = wp[ks * 64]; r0[d] = *(const v4i*)(a0p + ks * 32); r1[d] = *(const v4i*)(a1p + ks * 32);
-        }
-#pragma unroll 1
-        for (int k0 = 0; k0 < per; k0 += D) {
-#pragma unroll
-            for (int d = 0; d < D; ++d) {
-                const v4i w = rw[d], x0 = r0[d], x1 = r1[d];
-                const int ks = min(k0 + D + d, per - 1);                 // past the end: the last slab again (unused)
-                rw[d] = wp[ks * 64]; r0[d] = *(const v4i*)(a0p + ks * 32); r1[d] = *(const v4i*)(a1p + ks * 32);
-                if (k0 + d < per) {                                      // wave-uniform: the last turn may be partial
-                    c0 = mfma32(w, x0, c0);
-                    c1 = mfma32(w, x1, c1);
-                }
-            }
-        }
-        if (wave > 0) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                part[wave - 1][q][lane] = (v4i){c0[4 * q], c0[4 * q + 1], c0[4 * q + 2], c0[4 * q + 3]};
-                part[wave - 1][4 + q][lane] = (v4i){c1[4 * q], c1[4 * q + 1], c1[4 * q + 2], c1[4 * q + 3]};
-            }
-        }
-        __syncthreads();
-        if (wave == 0) {
-#pragma unroll
-            for (int w = 0; w < 3; ++w)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const v4i p0 = part[w][q][lane], p1 = part[w][4 + q][lane];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) { c0[4 * q + e] += p0[e]; c1[4 * q + e] += p1[e]; }
-                }
-            epilogue<EPI>(A, G, branch, row0 + j, nb, g, c0, pix[0], canon[0], gelu_lds);
-            epilogue<EPI>(A, G, branch, row0 + 32 + j, nb, g, c1, pix[1], canon[1], gelu_lds);
-        }
-        __syncthreads();                                              // the partial sums are free again
     }
 }
 
@@ -1570,22 +1497,19 @@ static void launch_gemm_e(const Geom& G, const GemmArgs& A0, hipStream_t st)
     int split = 1;                                   // split the channel blocks until the grid fills the chip
     while (gx * split < 1024 && split < NB) ++split;
     A.nb_per_block = (NB + split - 1) / split;
-    const bool long_k = A.K > 384;                  // the streaming form
-    const bool tile_form = tiles <= GEMM_TILE_MAX_TILES && (A.K <= GEMM_TILE_MAX_K || A.K % 1024 == 0);
-    if (long_k && A.K >= GEMM_SPLITK_MIN_K && (A.K / 32) % 4 == 0 && tiles <= GEMM_SPLITK_TILES) {     // few rows: split K over the waves of a workgroup
-        split = 1;
-        while (tiles * split < 1024 && split < NB) ++split;
-        A.nb_per_block = (NB + split - 1) / split;
-        hipLaunchKernelGGL((gemm_splitk_kernel<EPI>), dim3(tiles, (NB + A.nb_per_block - 1) / A.nb_per_block), dim3(256), 0, st, G, A);
-        return;
-    }
-    if (tile_form) {                                 // few rows: activations through LDS, output blocks over the waves (K above 2048 in
-                                                     // chunks of 1024; where the K split above applies it measures faster: 22.7 against 27.8 us at K = 3072)
-        int groups = std::max(1, std::min((NB + 3) / 4, (512 + tiles - 1) / tiles));
+    if (tiles <= GEMM_TILE_MAX_TILES && (A.K <= 4096 || A.K % 1024 == 0)) {
+        // few rows: the activation tile through LDS, output blocks over the waves and, in groups, over workgroups
+        const bool half = A.K > GEMM_TILE_MAX_K && A.K <= 4096;       // a long K stays whole in LDS on 32-row tiles (K = 3072 on 19 row
+                                                                      // tiles: 16.3 us; 64-row tiles in chunks of 1024: 27.8 us; K split over
+                                                                      // the four waves of a workgroup, operands straight from memory: 22.6 us)
+        const int nt = half ? G.rows_total / 32 : tiles;
+        const int groups = std::max(1, std::min((NB + 3) / 4, (512 + nt - 1) / nt));
         A.nb_per_block = ((NB + groups - 1) / groups + 3) / 4 * 4;
-        const dim3 grid(tiles, (NB + A.nb_per_block - 1) / A.nb_per_block);
-        if (A.K <= 384) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 384>), grid, dim3(256), 0, st, G, A);
-        else if (A.K <= 1024 || A.K > GEMM_TILE_MAX_K) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 1024>), grid, dim3(256), 0, st, G, A);
+        const dim3 grid(nt, (NB + A.nb_per_block - 1) / A.nb_per_block);
+        if (half && A.K <= 3072) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 3072, 32>), grid, dim3(256), 0, st, G, A);
+        else if (half) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 4096, 32>), grid, dim3(256), 0, st, G, A);
+        else if (A.K <= 384) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 384>), grid, dim3(256), 0, st, G, A);
+        else if (A.K <= 1024 || A.K > GEMM_TILE_MAX_K) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 1024>), grid, dim3(256), 0, st, G, A);   // above 4096: chunks of 1024
         else hipLaunchKernelGGL((gemm_tile_kernel<EPI, GEMM_TILE_MAX_K>), grid, dim3(256), 0, st, G, A);
         return;
     }

@@ -38,6 +38,7 @@ SMALL = [
     (1, 5, 6, 96, 3, 0, 0.0, 24, {}),                                                 # a map smaller than one window
     (2, 3, 20, 128, 4, 0, 0.5, 25, {}),                                               # one row of windows, mostly padding
     (3, 98, 98, 192, 6, 3, 0.5, 26, {}),                                              # 588 windows at six heads: one wave per head
+    (1, 14, 21, 1024, 32, 3, 0.5, 27, {}),                                            # the widest supported block (FC2 with K = 4096)
 ]
 
 
@@ -72,10 +73,10 @@ def test_independent_biases_per_branch(C, heads, bits, wbits, shift, fused):
     gh.assert_parity(res)
 
 
-@pytest.mark.parametrize("C,heads,mlp_ratio", [(96, 3, 3), (96, 3, 1), (192, 6, 3), (128, 4, 2), (96, 3, 8)])
+@pytest.mark.parametrize("C,heads,mlp_ratio", [(96, 3, 3), (96, 3, 1), (192, 6, 3), (128, 4, 2), (96, 3, 8), (768, 24, 8)])
 def test_other_mlp_ratios(C, heads, mlp_ratio):
     """FFN widths other than 4C run the seven-kernel path; hidden sizes that are not a whole number of
-    ring turns of the long-K GEMM (9 or 3 slabs of 32) included."""
+    ring turns of the GEMM (9 or 3 slabs of 32) included, and K = 6144, which goes through LDS in chunks."""
     spec, inp, x, k = _case(2, 20, 27, C, heads, 3, 0.5, 52, blobs=True, mlp_ratio=mlp_ratio)
     print("mlp_ratio", mlp_ratio, "C", C, flush=True)
     res = gh.compare_block(inp, x, k)
@@ -84,11 +85,10 @@ def test_other_mlp_ratios(C, heads, mlp_ratio):
 
 
 def test_long_k_on_a_few_hundred_row_tiles():
-    """FC2 with K = 3072 on 111 row tiles: too many for the split of K over a workgroup's waves, so the GEMM that
-    stages the activation tile in LDS takes K in chunks."""
+    """FC2 with K = 3072 on 111 64-row tiles: the GEMM keeps the whole K of a 32-row tile in LDS (222 tiles)."""
     spec, inp, x, k = _case(2, 50, 60, 384, 12, 3, 0.5, 54, blobs=True, mlp_ratio=8)
     assert spec.B * spec.nW * 49 > 64 * 64
-    print("long K, chunked", flush=True)
+    print("long K on many tiles", flush=True)
     res = gh.compare_block(inp, x, k)
     print(res, flush=True)
     gh.assert_parity(res)
