@@ -33,6 +33,7 @@ struct GemmArgs {
     const int8_t* A;                 // activations [rows,K] row-major
     const v4i* Wp;                   // packed weights [N/32][K/32][64 lanes] x 16 bytes
     int K, N, nb_per_block;
+    int kchunk;                      // bytes of K staged in LDS at a time (a divisor of K; set by the launcher)
     const float* m[2];               // s_in * s_w[n] per branch
     const float* bias[2];
     const int* negcorr[2];           // -zp_in * sum_k W[n,k]

@@ -2,7 +2,7 @@
 //   score_kernel      window importance = squared L2 norm            (Sec. 3.2)
 //   select_kernel     top-k partition into high / low groups         (Sec. 3.2)
 //   ln_quant_kernel   gather (shift folded in) + LayerNorm + quantize, also LN2
-//   gemm_kernel       int8 MFMA linear layers with fused epilogues   (shadow layers)
+//   gemm_tile_kernel  int8 MFMA linear layers with fused epilogues   (shadow layers)
 //   attn_kernel       per (window, head): QK^T, bias+mask, softmax, P.V
 // Arithmetic that decides an integer code follows the pinned binary32 sequences
 // of mixaq_dev.h; reductions feeding a code run in binary64.
@@ -290,88 +290,14 @@ __device__ __forceinline__ void epilogue(const GemmArgs& A, const Geom& G, int b
     }
 }
 
-constexpr int GEMM_RING = 4;          // operand slabs in flight per wave in the long-K GEMM (6 and 8 measured: no faster)
-template <int KS, int EPI>      // KS = K/32 when the activation fragments fit in registers, 0 = stream them
-__global__ __launch_bounds__(256) void gemm_kernel(Geom G, GemmArgs A)
-{
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 31, g = lane >> 5;
-    __shared__ float4 gtab[EPI == EPI_FC1 ? GELU_K : 1];
-    if (EPI == EPI_FC1) {
-        gelu_stage_table(gtab, A.gelu_tab, threadIdx.x, 256);
-        __syncthreads();
-    }
-    const float4* gelu_lds = gtab;
-    const int tile = blockIdx.x * 4 + wave;
-    if (tile * ROW_TILE >= G.rows_total) return;
-    const int row0 = tile * ROW_TILE;
-    const int branch = row0 >= G.base_lo ? 1 : 0;
-    const int K = A.K, ks_n = K / 32, NB = A.N / 32;
-    const int nb_lo = blockIdx.y * A.nb_per_block, nb_hi = min(nb_lo + A.nb_per_block, NB);
-    const int8_t* a0p = A.A + (size_t)(row0 + j) * K + g * 16;
-    const int8_t* a1p = a0p + (size_t)32 * K;
-    int pix[2] = {0, 0}, canon[2];
-    canon[0] = A.row_canon[row0 + j]; canon[1] = A.row_canon[row0 + 32 + j];
-    if (EPI == EPI_PROJ || EPI == EPI_FC2) { pix[0] = A.row_pix[row0 + j]; pix[1] = A.row_pix[row0 + 32 + j]; }
-    v4i b0[KS > 0 ? KS : 1], b1[KS > 0 ? KS : 1];
-    if (KS > 0) {
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) { b0[ks] = *(const v4i*)(a0p + ks * 32); b1[ks] = *(const v4i*)(a1p + ks * 32); }
-    }
-    for (int nb = nb_lo; nb < nb_hi; ++nb) {
-        v16i c0, c1;
-        {   // accumulators start at -zp_in * colsum(W[n,:])
-            const int* nc = A.negcorr[branch] + nb * 32 + g * 4;
-#pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                int4 t = *(const int4*)(nc + qd * 8);
-                c0[qd * 4 + 0] = t.x; c0[qd * 4 + 1] = t.y; c0[qd * 4 + 2] = t.z; c0[qd * 4 + 3] = t.w;
-            }
-            c1 = c0;
-        }
-        const v4i* wp = A.Wp + (size_t)nb * ks_n * 64 + lane;
-        if (KS > 0) {
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                v4i w = wp[ks * 64];
-                c0 = mfma32(w, b0[ks], c0);
-                c1 = mfma32(w, b1[ks], c1);
-            }
-        } else {                      // long K: operands stream from L2 through a ring, D slabs ahead
-            constexpr int D = GEMM_RING;
-            v4i rw[D], r0[D], r1[D];
-#pragma unroll
-            for (int d = 0; d < D; ++d) {                                // K may hold fewer than D slabs: re-read the last one (unused)
-                const int ks = min(d, ks_n - 1);
-                rw[d] = wp[ks * 64]; r0[d] = *(const v4i*)(a0p + ks * 32); r1[d] = *(const v4i*)(a1p + ks * 32);
-            }
-#pragma unroll 1
-            for (int k0 = 0; k0 < ks_n; k0 += D) {
-#pragma unroll
-                for (int d = 0; d < D; ++d) {
-                    const v4i w = rw[d], x0 = r0[d], x1 = r1[d];
-                    const int ks = min(k0 + D + d, ks_n - 1);            // past the end: the last slab again (unused)
-                    rw[d] = wp[ks * 64]; r0[d] = *(const v4i*)(a0p + ks * 32); r1[d] = *(const v4i*)(a1p + ks * 32);
-                    if (k0 + d < ks_n) {                                 // wave-uniform: the last turn may be partial
-                        c0 = mfma32(w, x0, c0);
-                        c1 = mfma32(w, x1, c1);
-                    }
-                }
-            }
-        }
-        epilogue<EPI>(A, G, branch, row0 + j, nb, g, c0, pix[0], canon[0], gelu_lds);
-        epilogue<EPI>(A, G, branch, row0 + 32 + j, nb, g, c1, pix[1], canon[1], gelu_lds);
-    }
-}
-
-// Few rows (the widest stages at batch 1: 20 row tiles at C = 768): one workgroup per 64-row tile and group of
-// output blocks.  The tile's activation rows are read once, 16 contiguous bytes per lane, and laid out in LDS as
+// One workgroup per 64-row tile and group of output blocks (all of them once the tiles alone fill the chip; on few
+// rows, e.g. 20 row tiles at C = 768 and batch 1, groups of four).  The tile's activation rows are read once, 16 contiguous bytes per lane, and laid out in LDS as
 // MFMA operand fragments (the row-major codes read directly as operands are 16 bytes from each of 32 rows per
 // load, a quarter of every cache line touched); wave w computes the output blocks first + w, first + w + 4, ...
 // of the group: weight fragments stream through a ring of loads in flight, the B operand comes from LDS.
 // K up to 2048 stays whole in LDS for a 64-row tile, K up to 4096 for a 32-row tile; longer K passes in chunks.
-constexpr int GEMM_TILE_MAX_TILES = 256;   // up to this many row tiles (above, the chip is full without the split over output blocks)
 constexpr int GEMM_TILE_MAX_K = 2048;      // 64 rows x K bytes of LDS
-// KMAX: bytes of K the instantiation's LDS holds per row (a longer K goes through in chunks of KMAX); RT: rows per tile,
+// KMAX: bytes of K the instantiation's LDS holds per row (a longer K goes through in chunks of A.kchunk <= KMAX); RT: rows per tile,
 // 64 or, so that a long K fits LDS whole, 32
 template <int EPI, int KMAX, int RT = ROW_TILE>
 __global__ __launch_bounds__(256) void gemm_tile_kernel(Geom G, GemmArgs A)
@@ -384,7 +310,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(Geom G, GemmArgs A)
     const int row0 = blockIdx.x * RT;
     const int branch = row0 >= G.base_lo ? 1 : 0;
     const int K = A.K, ks_n = K / 32, NB = A.N / 32;
-    const int kch = min(K, KMAX), cs = kch / 32, n_ch = K / kch, per_row = kch / 16;   // chunk bytes, slabs per chunk, chunks
+    const int kch = A.kchunk, cs = kch / 32, n_ch = K / kch, per_row = kch / 16;       // chunk bytes (a divisor of K, at most KMAX), slabs per chunk, chunks
     auto stage = [&](int ch) {     // piece (row r, 16-byte chunk q) -> fragment (r/32, q/2), lane (r%32, q%2)
         for (int p = tid; p < RT * per_row; p += 256) {
             const int r = p / per_row, q = p - r * per_row;
@@ -1493,35 +1419,22 @@ static void launch_gemm_e(const Geom& G, const GemmArgs& A0, hipStream_t st)
 {
     GemmArgs A = A0;
     if (G.rows_total == 0) return;
-    const int tiles = G.rows_total / ROW_TILE, gx = (tiles + 3) / 4, NB = A.N / 32;
-    int split = 1;                                   // split the channel blocks until the grid fills the chip
-    while (gx * split < 1024 && split < NB) ++split;
-    A.nb_per_block = (NB + split - 1) / split;
-    if (tiles <= GEMM_TILE_MAX_TILES && (A.K <= 4096 || A.K % 1024 == 0)) {
-        // few rows: the activation tile through LDS, output blocks over the waves and, in groups, over workgroups
-        const bool half = A.K > GEMM_TILE_MAX_K && A.K <= 4096;       // a long K stays whole in LDS on 32-row tiles (K = 3072 on 19 row
-                                                                      // tiles: 16.3 us; 64-row tiles in chunks of 1024: 27.8 us; K split over
-                                                                      // the four waves of a workgroup, operands straight from memory: 22.6 us)
-        const int nt = half ? G.rows_total / 32 : tiles;
-        const int groups = std::max(1, std::min((NB + 3) / 4, (512 + nt - 1) / nt));
-        A.nb_per_block = ((NB + groups - 1) / groups + 3) / 4 * 4;
-        const dim3 grid(nt, (NB + A.nb_per_block - 1) / A.nb_per_block);
-        if (half && A.K <= 3072) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 3072, 32>), grid, dim3(256), 0, st, G, A);
-        else if (half) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 4096, 32>), grid, dim3(256), 0, st, G, A);
-        else if (A.K <= 384) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 384>), grid, dim3(256), 0, st, G, A);
-        else if (A.K <= 1024 || A.K > GEMM_TILE_MAX_K) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 1024>), grid, dim3(256), 0, st, G, A);   // above 4096: chunks of 1024
-        else hipLaunchKernelGGL((gemm_tile_kernel<EPI, GEMM_TILE_MAX_K>), grid, dim3(256), 0, st, G, A);
-        return;
-    }
-    dim3 grid(gx, (NB + A.nb_per_block - 1) / A.nb_per_block);
-    switch (A.K) {
-        case 96: hipLaunchKernelGGL((gemm_kernel<3, EPI>), grid, dim3(256), 0, st, G, A); break;
-        case 128: hipLaunchKernelGGL((gemm_kernel<4, EPI>), grid, dim3(256), 0, st, G, A); break;
-        case 192: hipLaunchKernelGGL((gemm_kernel<6, EPI>), grid, dim3(256), 0, st, G, A); break;
-        case 256: hipLaunchKernelGGL((gemm_kernel<8, EPI>), grid, dim3(256), 0, st, G, A); break;
-        case 384: hipLaunchKernelGGL((gemm_kernel<12, EPI>), grid, dim3(256), 0, st, G, A); break;
-        default: hipLaunchKernelGGL((gemm_kernel<0, EPI>), grid, dim3(256), 0, st, G, A); break;
-    }
+    const int tiles = G.rows_total / ROW_TILE, NB = A.N / 32;
+    // the activation tile through LDS, output blocks over the waves and, while the grid is small, in groups over workgroups
+    const bool half = A.K > GEMM_TILE_MAX_K && A.K <= 4096;           // a long K stays whole in LDS on 32-row tiles (K = 3072 on 19 row
+                                                                      // tiles: 16.3 us; 64-row tiles in chunks of 1024: 27.8 us)
+    A.kchunk = A.K;
+    if (A.K > 4096)                                                   // chunks of whole ring turns (256 bytes of K each): the largest such size up to
+        for (A.kchunk = 1024; A.kchunk > 256 && A.K % A.kchunk; A.kchunk -= 256) {}   // 1024 that divides K (K = 768 r or 1024 r here: 256 always does)
+    const int nt = half ? G.rows_total / 32 : tiles;
+    const int groups = std::max(1, std::min((NB + 3) / 4, (512 + nt - 1) / nt));
+    A.nb_per_block = ((NB + groups - 1) / groups + 3) / 4 * 4;
+    const dim3 grid(nt, (NB + A.nb_per_block - 1) / A.nb_per_block);
+    if (half && A.K <= 3072) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 3072, 32>), grid, dim3(256), 0, st, G, A);
+    else if (half) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 4096, 32>), grid, dim3(256), 0, st, G, A);
+    else if (A.K <= 384) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 384>), grid, dim3(256), 0, st, G, A);
+    else if (A.K <= 1024 || A.K > GEMM_TILE_MAX_K) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 1024>), grid, dim3(256), 0, st, G, A);   // above 4096: chunks of 1024
+    else hipLaunchKernelGGL((gemm_tile_kernel<EPI, GEMM_TILE_MAX_K>), grid, dim3(256), 0, st, G, A);
 }
 
 void launch_gemm(const Geom& G, const GemmArgs& A, int epi, hipStream_t st)
