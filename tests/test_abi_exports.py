@@ -38,3 +38,12 @@ def test_host_only_entry_points():
         assert False
     except M.MixaqError as e:
         assert e.code == -2 and "keep_ratio" in str(e)
+
+
+def test_benchmark_refuses_more_than_one_gpu():
+    """The path has no collectives: `bench.py --gpus N` with N above 1 exits with a message and measures nothing."""
+    import subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
