@@ -42,12 +42,13 @@ SMALL = [
 ]
 
 
-@pytest.mark.parametrize("fused", [True, False])
-@pytest.mark.parametrize("B,H,W,C,heads,shift,keep,seed,kw", SMALL)
+# both implementations where both exist: the fused kernels cover C <= 384, the seven-kernel path every width
+BLOCK_CASES = [case + (fused,) for case in SMALL for fused in (True, False) if not (fused and case[3] > 384)]
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,shift,keep,seed,kw,fused", BLOCK_CASES)
 def test_block_matches_oracle(B, H, W, C, heads, shift, keep, seed, kw, fused):
     """fused: the window and token kernels (C <= 384); otherwise the seven-kernel path."""
-    if fused and C > 384:
-        pytest.skip("the fused kernels cover C <= 384")
     spec, inp, x, k = _case(B, H, W, C, heads, shift, keep, seed, **kw)
     print("case", B, H, W, C, heads, shift, keep, seed, kw, "fused", fused, flush=True)
     res = gh.compare_block(inp, x, k, fused=fused)
@@ -55,14 +56,16 @@ def test_block_matches_oracle(B, H, W, C, heads, shift, keep, seed, kw, fused):
     gh.assert_parity(res)
 
 
-@pytest.mark.parametrize("fused", [True, False])
-@pytest.mark.parametrize("shift", [0, 3])
-@pytest.mark.parametrize("C,heads,bits,wbits", [(96, 3, (8, 4), 8), (384, 12, (8, 4), 8), (768, 24, (4, 2), 4)])
+BIAS_CASES = [(C, heads, bits, wbits, shift, fused)
+              for (C, heads, bits, wbits) in [(96, 3, (8, 4), 8), (384, 12, (8, 4), 8), (768, 24, (4, 2), 4)]
+              for shift in (0, 3) for fused in (True, False) if not (fused and C > 384)]
+
+
+@pytest.mark.parametrize("C,heads,bits,wbits,shift,fused", BIAS_CASES)
 def test_independent_biases_per_branch(C, heads, bits, wbits, shift, fused):
     """PTQ variant (Sec. 4.3, PTQ setup): the low branch has biases of its own, visibly different from the
-    high branch's; every tap must follow the bias of the row's branch."""
-    if fused and C > 384:
-        pytest.skip("the fused kernels cover C <= 384")
+    high branch's; every tap must follow the bias of the row's branch (both implementations up to C = 384, the
+    seven-kernel path, the only one there, at C = 768)."""
     spec, inp, x, k = _case(2, 20, 27, C, heads, shift, 0.4, 51, blobs=True, bits=bits, wbits=wbits,
                             per_branch_bias=True, bias_std=0.1)
     for n in ("b_qkv", "b_proj", "b_fc1", "b_fc2"):
