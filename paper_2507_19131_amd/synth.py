@@ -144,14 +144,17 @@ def make_feature_map(spec, seed, blobs=False, outlier_channels=False):
         rr, cc = np.meshgrid(np.arange(spec.H), np.arange(spec.W), indexing="ij")
         for b in range(spec.B):
             cover = np.zeros((spec.H, spec.W), dtype=bool)
-            while cover.mean() < 0.30:
+            rejected = 0                     # on a map of a few pixels no further region may fit under the limit: give up then
+            while cover.mean() < 0.30 and rejected < 200:
                 cy, cx = brng.uniform(0, spec.H), brng.uniform(0, spec.W)
                 ay = brng.uniform(0.04, 0.12) * spec.H + 2
                 ax = brng.uniform(0.04, 0.12) * spec.W + 2
                 m = ((rr - cy) / ay) ** 2 + ((cc - cx) / ax) ** 2 <= 1.0
                 m &= ~cover
                 if cover.mean() + m.mean() > 0.31:
+                    rejected += 1
                     continue
+                rejected = rejected + 1 if not m.any() else 0    # a region that adds no pixel is no progress either
                 u = brng.standard_normal(spec.C).astype(np.float32)
                 x[b][m] = np.float32(4.0) * x[b][m] + np.float32(3.0) * u
                 cover |= m
