@@ -183,8 +183,13 @@ int mixaq_block_forward_scored(const mixaq_block *blk, const float *x, const dou
  * overlap).  scores (device double [B,nW]) and perm (device int32 [B,nW]) are caller-owned scratch
  * that hold the stage's scores and selection list afterwards.  The workspace must satisfy
  * mixaq_block_workspace_bytes of the stage's blocks (equal shapes give equal sizes).  All work is
- * enqueued on `stream`; nothing is allocated.  MIXAQ_E_SHAPE if the blocks disagree on the shape
- * or a count is out of range, MIXAQ_E_NULL for missing pointers. */
+ * ordered on `stream`; nothing is allocated.  A batch of small maps (B >= 2, at most 512 windows in
+ * all, fused kernels) runs as two chains of blocks, one per half of the images (they are independent
+ * through the whole stage): the second chain is enqueued on a stream of the library's own that
+ * starts after the work already on `stream` and that `stream` waits for before the call's work
+ * counts as done, so the caller sees the same ordering as without it; under stream capture the
+ * stage stays on `stream` alone.  MIXAQ_E_SHAPE if the blocks disagree on the shape or a count is
+ * out of range, MIXAQ_E_NULL for missing pointers. */
 int mixaq_stage_forward(mixaq_block *const *blocks, int32_t n_blocks, const float *x, const int32_t *k_high,
                         const int32_t *k_low, float *y, float *tmp, double *scores, int32_t *perm, void *workspace,
                         size_t workspace_bytes, void *stream);

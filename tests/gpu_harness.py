@@ -51,6 +51,15 @@ class GpuBlock:
         return y
 
 
+def _forward_pruned(self, x, perm, k_high, k_low):
+    y = torch.full_like(x, float("nan"))
+    M.mixaq_block_forward_pruned(self.blk, x, perm, k_high, k_low, y, self.ws)
+    return y
+
+
+GpuBlock.forward_pruned = _forward_pruned
+
+
 def compare_block(inp, x_np, k_high, shift=None, perm_np=None, taps="all", fused=None):
     """Oracle vs GPU on one block: returns a dict of mismatch counts / errors; asserts nothing."""
     spec = inp.spec

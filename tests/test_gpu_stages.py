@@ -130,6 +130,51 @@ def test_stage_entry_point_with_a_ratio_per_pair_and_pruning(fused):
     assert np.array_equal(y_gpu, cur)
 
 
+@pytest.mark.parametrize("B,C,heads", [(2, 384, 12), (3, 96, 3), (5, 192, 6)])
+def test_stage_on_a_batch_of_small_maps_runs_as_two_chains(B, C, heads):
+    """A batch of small maps (at most 512 windows in all) goes through the stage call as two chains of blocks, one per
+    half of the images (uneven halves for an odd batch), the second on the library's side stream; the result is the
+    oracle's, the same bits as block after block on the whole batch, and repeated calls agree."""
+    spec = synth.BlockSpec(B, 30, 37, C, heads)
+    shifts = [0, 3, 0, 3]
+    assert B * spec.nW <= 512
+    x_np = synth.make_feature_map(spec, 78, blobs=True)
+    inputs = [synth.make_block_inputs(spec, 800 + i) for i in range(len(shifts))]
+    k_high, k_low = [spec.nW // 2, spec.nW // 3], [spec.nW - spec.nW // 2, spec.nW // 3]      # the second pair prunes a third
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(x_np).to(dev)
+    print("two chains, batch", B, "C", C, flush=True)
+    blocks = [gh.GpuBlock(inp, shift) for inp, shift in zip(inputs, shifts)]
+    try:
+        y, tmp = torch.full_like(x, float("nan")), torch.empty_like(x)
+        scores = torch.empty((B, spec.nW), dtype=torch.float64, device=dev)
+        perm = torch.full((B, spec.nW), -1, dtype=torch.int32, device=dev)
+        handles = [gb.blk for gb in blocks]
+        M.mixaq_stage_forward(handles, x, k_high, k_low, y, tmp, scores, perm, blocks[0].ws)
+        torch.cuda.synchronize()
+        y1, perm1 = y.clone(), perm.clone()
+        for _ in range(3):                                         # the side stream joins every call: no call sees the last one's state
+            M.mixaq_stage_forward(handles, x, k_high, k_low, y, tmp, scores, perm, blocks[0].ws)
+        torch.cuda.synchronize()
+        assert torch.equal(y, y1) and torch.equal(perm, perm1)
+        cur = x                                                    # block after block on the whole batch, one stream
+        for i, gb in enumerate(blocks):
+            cur = gb.forward_pruned(cur, perm, k_high[i // 2], k_low[i // 2])
+        torch.cuda.synchronize()
+        assert torch.equal(cur, y1)
+        y_gpu, perm_gpu = y1.cpu().numpy(), perm1.cpu().numpy()
+    finally:
+        for gb in blocks:
+            gb.close()
+    sc_o = O.score_windows(inputs[0], x_np)
+    cur = x_np
+    for i, (inp, shift) in enumerate(zip(inputs, shifts)):
+        perm_o = O.select_windows(sc_o, k_high[i // 2], k_low=k_low[i // 2])
+        assert np.array_equal(perm_gpu, perm_o)
+        cur, _ = O.block_forward(inp, cur, perm_o, k_high[i // 2], shift, threads=16, k_low=k_low[i // 2])
+    assert np.array_equal(y_gpu, cur)
+
+
 def test_stage_on_a_side_stream_matches_the_default_stream():
     """All work of a call is enqueued on the stream it is given: a stage run on a second stream (default
     priority) while the default stream is kept busy gives the same bits."""
