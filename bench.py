@@ -214,7 +214,7 @@ class Stage:
                    pct_int8_mfma_peak=round(100 * tops / PEAK_INT8_TOPS, 3),
                    ideal_windows_per_s=round(ideal_windows_per_s(spec.C), 1),
                    frac_of_fused_ideal=round(wps / ideal_windows_per_s(spec.C), 5))
-        if spec.B >= 2 and self.n_win <= 512 and spec.C <= 384 and len(self.blocks) > 1:
+        if spec.B >= 2 and self.n_win <= 4096 and spec.C <= 384 and len(self.blocks) > 1:
             out["two_chains"] = ("the stage call runs the two halves of the batch as two chains of blocks on two streams; the per-kernel "
                                  "durations below are whole-batch launches on one stream and add up to more than ms_per_pass")
         if kernels:

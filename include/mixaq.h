@@ -183,7 +183,7 @@ int mixaq_block_forward_scored(const mixaq_block *blk, const float *x, const dou
  * overlap).  scores (device double [B,nW]) and perm (device int32 [B,nW]) are caller-owned scratch
  * that hold the stage's scores and selection list afterwards.  The workspace must satisfy
  * mixaq_block_workspace_bytes of the stage's blocks (equal shapes give equal sizes).  All work is
- * ordered on `stream`; nothing is allocated.  A batch of small maps (B >= 2, at most 512 windows in
+ * ordered on `stream`; nothing is allocated.  A batch of small maps (B >= 2, at most 4096 windows in
  * all, fused kernels) runs as two chains of blocks, one per half of the images (they are independent
  * through the whole stage): the second chain is enqueued on a stream of the library's own that
  * starts after the work already on `stream` and that `stream` waits for before the call's work

@@ -262,9 +262,10 @@ int check_qparam(const mixaq_qparam& q, int bits, const char* name)
     return MIXAQ_OK;
 }
 
-// Two chains pay when every kernel of the stage leaves CUs idle: a batch of at least two maps with at most this many
-// windows in all, on the fused kernels (config 3: 2 x 96 windows at C = 384, 0.34 instead of 0.41 ms per stage pass).
-constexpr int STAGE_SPLIT_MAX_WINDOWS = 512;
+// Two chains pay while the kernels of the stage leave CUs idle for part of their time: a batch of at least two maps
+// with at most this many windows in all, on the fused kernels (config 3, 2 x 96 windows at C = 384: 0.36 instead of
+// 0.41 ms per stage pass; 2 x 1392 windows at C = 96: 10 % faster; 4 x 1392: 4 %, no longer taken).
+constexpr int STAGE_SPLIT_MAX_WINDOWS = 4096;
 bool stage_splits(const mixaq_block* b)
 {
     return b->d.B >= 2 && b->d.B * b->nW <= STAGE_SPLIT_MAX_WINDOWS && b->fused_window && b->fused_token;

@@ -132,12 +132,12 @@ def test_stage_entry_point_with_a_ratio_per_pair_and_pruning(fused):
 
 @pytest.mark.parametrize("B,C,heads", [(2, 384, 12), (3, 96, 3), (5, 192, 6)])
 def test_stage_on_a_batch_of_small_maps_runs_as_two_chains(B, C, heads):
-    """A batch of small maps (at most 512 windows in all) goes through the stage call as two chains of blocks, one per
+    """A batch of small maps (at most 4096 windows in all) goes through the stage call as two chains of blocks, one per
     half of the images (uneven halves for an odd batch), the second on the library's side stream; the result is the
     oracle's, the same bits as block after block on the whole batch, and repeated calls agree."""
     spec = synth.BlockSpec(B, 30, 37, C, heads)
     shifts = [0, 3, 0, 3]
-    assert B * spec.nW <= 512
+    assert B * spec.nW <= 4096
     x_np = synth.make_feature_map(spec, 78, blobs=True)
     inputs = [synth.make_block_inputs(spec, 800 + i) for i in range(len(shifts))]
     k_high, k_low = [spec.nW // 2, spec.nW // 3], [spec.nW - spec.nW // 2, spec.nW // 3]      # the second pair prunes a third
@@ -173,6 +173,32 @@ def test_stage_on_a_batch_of_small_maps_runs_as_two_chains(B, C, heads):
         assert np.array_equal(perm_gpu, perm_o)
         cur, _ = O.block_forward(inp, cur, perm_o, k_high[i // 2], shift, threads=16, k_low=k_low[i // 2])
     assert np.array_equal(y_gpu, cur)
+
+
+def test_two_chains_at_config2_shape_on_two_maps():
+    """2 x 1392 windows at C = 96: the largest kind of batch the stage call still runs as two chains."""
+    import dataclasses
+    wl = synth.workload("cfg2")
+    st = wl["stages"][0]
+    spec = dataclasses.replace(st["spec"], B=2)
+    assert spec.B * spec.nW <= 4096
+    y_blocks, y_or, perm_blocks, perm_or = run_stage(spec, st["shifts"], wl["keep"][0], wl["seed"], wl["blobs"], wl["outliers"], wl.get("ranges"))
+    check(y_blocks, y_or, perm_blocks, perm_or)
+    k = M.mixaq_keep_count(spec.nW, wl["keep"][0])
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(synth.make_feature_map(spec, wl["seed"], blobs=wl["blobs"], outlier_channels=wl["outliers"])).to(dev)
+    inputs = [synth.make_block_inputs(spec, wl["seed"] + 10 * i, ranges=wl.get("ranges")) for i in range(len(st["shifts"]))]
+    blocks = [gh.GpuBlock(inp, shift) for inp, shift in zip(inputs, st["shifts"])]
+    try:
+        y, tmp = torch.full_like(x, float("nan")), torch.empty_like(x)
+        scores = torch.empty((spec.B, spec.nW), dtype=torch.float64, device=dev)
+        perm = torch.empty((spec.B, spec.nW), dtype=torch.int32, device=dev)
+        M.mixaq_stage_forward([gb.blk for gb in blocks], x, [k], None, y, tmp, scores, perm, blocks[0].ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy(), y_or) and np.array_equal(perm.cpu().numpy(), perm_or)
+    finally:
+        for gb in blocks:
+            gb.close()
 
 
 def test_stage_on_a_side_stream_matches_the_default_stream():
