@@ -744,7 +744,12 @@ int mixaq_stage_forward(mixaq_block* const* blocks, int32_t n_blocks, const floa
     hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
     bool split = n_blocks > 1 && b0->side_stream != nullptr;
     for (int i = 0; split && i < n_blocks; ++i) split = blocks[i]->fused_window && blocks[i]->fused_token;
-    if (split && (hipStreamIsCapturing(st, &capturing) != hipSuccess || capturing != hipStreamCaptureStatusNone)) split = false;
+    if (split) {
+        if (hipStreamIsCapturing(st, &capturing) != hipSuccess) {
+            (void)hipGetLastError();                                  // not to be mistaken for a launch error later
+            split = false;
+        } else if (capturing != hipStreamCaptureStatusNone) split = false;
+    }
     if (split) {
         Workspace w;
         n_parts = 2;
