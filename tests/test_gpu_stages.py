@@ -236,24 +236,33 @@ def test_stage_on_a_side_stream_matches_the_default_stream():
             gb.close()
 
 
-def test_config2_stage_call_as_the_benchmark_launches_it():
-    """BASELINE config 2 at full size through mixaq_stage_forward, the one call a benchmark step makes
-    (score, selection inside the first block's first kernel, list handed to the shifted block)."""
-    wl = synth.workload("cfg2")
-    st = wl["stages"][0]
-    spec = st["spec"]
-    x_np = synth.make_feature_map(spec, wl["seed"], blobs=wl["blobs"], outlier_channels=wl["outliers"])
-    inputs = [synth.make_block_inputs(spec, wl["seed"] + 10 * i) for i, _ in enumerate(st["shifts"])]
-    k = M.mixaq_keep_count(spec.nW, wl["keep"][0])
+BENCH_STAGES = [("cfg1", 0), ("cfg2", 0), ("cfg3", 0), ("cfg4", 1), ("cfg4", 2), ("cfg4", 3), ("cfg5", 0), ("cfg5", 1)]
+
+
+@pytest.mark.parametrize("name,stage", BENCH_STAGES, ids=[f"{n}-stage{s + 1}" for n, s in BENCH_STAGES])
+def test_stage_call_as_the_benchmark_launches_it(name, stage):
+    """Every benchmark workload at full size through mixaq_stage_forward, the one call a benchmark step makes
+    (score, selection inside the first block's first kernel, list handed on to the later blocks; config 3's two
+    maps go through it as two chains, config 4's last stage on the seven-kernel path)."""
+    wl = synth.workload(name)
+    st = wl["stages"][stage]
+    spec, shifts = st["spec"], st["shifts"]
+    keep = wl["keep"][len(wl["keep"]) // 2]
+    seed = wl["seed"] + stage
+    print("stage call", name, "stage", stage + 1, "C", spec.C, "B", spec.B, "windows", spec.B * spec.nW, flush=True)
+    x_np = synth.make_feature_map(spec, seed, blobs=wl["blobs"], outlier_channels=wl["outliers"])
+    inputs = [synth.make_block_inputs(spec, seed + 10 * i, ranges=wl.get("ranges")) for i, _ in enumerate(shifts)]
+    k = M.mixaq_keep_count(spec.nW, keep)
+    pairs = (len(shifts) + 1) // 2
     dev = torch.device("cuda:0")
     x = torch.from_numpy(x_np).to(dev)
-    blocks = [gh.GpuBlock(inp, shift) for inp, shift in zip(inputs, st["shifts"])]
+    blocks = [gh.GpuBlock(inp, shift) for inp, shift in zip(inputs, shifts)]
     try:
         y, tmp = torch.full_like(x, float("nan")), torch.empty_like(x)
         scores = torch.empty((spec.B, spec.nW), dtype=torch.float64, device=dev)
         perm = torch.empty((spec.B, spec.nW), dtype=torch.int32, device=dev)
         for _ in range(3):                                          # repeated calls reuse workspace, scores and list
-            M.mixaq_stage_forward([gb.blk for gb in blocks], x, [k], None, y, tmp, scores, perm, blocks[0].ws)
+            M.mixaq_stage_forward([gb.blk for gb in blocks], x, [k] * pairs, None, y, tmp, scores, perm, blocks[0].ws)
         torch.cuda.synchronize()
         y_gpu, perm_gpu = y.cpu().numpy(), perm.cpu().numpy()
     finally:
@@ -261,7 +270,7 @@ def test_config2_stage_call_as_the_benchmark_launches_it():
             gb.close()
     perm_o = O.select_windows(O.score_windows(inputs[0], x_np), k)
     cur = x_np
-    for inp, shift in zip(inputs, st["shifts"]):
+    for inp, shift in zip(inputs, shifts):
         cur, _ = O.block_forward(inp, cur, perm_o, k, shift, threads=16)
     check(y_gpu, cur, perm_gpu, perm_o)
     assert np.array_equal(y_gpu, cur)
