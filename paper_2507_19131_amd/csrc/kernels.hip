@@ -600,7 +600,7 @@ struct WinCfg {
     static constexpr int GPW = 64 / LPT;                             // groups (tokens) per wave
     static constexpr int NV = NH * HG * 32 / (4 * LPT);              // float4 per lane = 8 * HG / QS
 };
-constexpr int win_waves_per_eu(int NH, int HG, int QS) { return QS == 2 ? 4 : (HG == 2 && NH <= 8) ? 2 : WIN_WAVES_PER_EU; }
+constexpr int win_waves_per_eu(int NH, int HG, int QS) { return QS == 2 ? (NH * HG > 8 ? 3 : 4) : (HG == 2 && NH <= 8) ? 2 : WIN_WAVES_PER_EU; }
 
 // word offsets inside the window kernel's parameter block of one branch (see WinArgs::params)
 template <int C> struct WinPrm {
@@ -1453,7 +1453,9 @@ void launch_gemm(const Geom& G, const GemmArgs& A, int epi, hipStream_t st)
 bool fused_window_supported(int C) { return C == 96 || C == 128 || C == 192 || C == 256 || C == 384; }
 bool fused_token_supported(int C, int mlp_ratio) { return (C == 96 || C == 128 || C == 192 || C == 256 || C == 384) && mlp_ratio == 4; }
 
-constexpr int WINDOW_SPLIT_SMALL = 128;      // C = 384: up to this many windows, two workgroups share a window's heads
+// C = 384: up to this many windows, two workgroups share a window's heads, each with a pair of waves per head (twelve
+// waves: 15.7 instead of 16.8 us on 96 windows with one wave per head, and 22.8 us for one twelve-head workgroup per window)
+constexpr int WINDOW_SPLIT_SMALL = 128;
 // Up to this many windows a pair of waves shares a head.  The pair form has the shorter chain of dependent steps
 // (a workgroup alone on its CU: 9.5 instead of 11.2 us at C = 96) but 15 % more vector and 80 % more scalar
 // instructions per window, so it loses once the CUs are full (1392 windows at C = 96: 31 instead of 28.3 us;
@@ -1490,7 +1492,7 @@ void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
             WIN_CASE(6, 1, 1);
         case 8: WIN_CASE(8, 1, 1);
         case 12:
-            if (n_wg <= WINDOW_SPLIT_SMALL) { WIN_CASE(6, 2, 1); }
+            if (n_wg <= WINDOW_SPLIT_SMALL) { WIN_CASE(6, 2, 2); }
             WIN_CASE(12, 1, 1);
         default: break;
     }
