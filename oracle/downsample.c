@@ -23,10 +23,12 @@
  * [N][K] int8 codes with per-output-channel scales s_w.  Optional taps: codes
  * [tokens][K] and acc [tokens][N] (acc is the zero-point corrected sum).
  *
- * Parity status: gather order, LayerNorm and the integer sums are pinned by
- * tests against numpy (slicing, float64 LayerNorm, int64 matmul); the values of
- * a quantized output have no printed example in the paper: parity unpinned
- * beyond those pins.
+ * Parity status: every step is pinned by tests against numpy: gather order
+ * (slicing), codes (patch embedding: exact rational quantization of every
+ * value; patch merging: within half a step of a float64 LayerNorm), integer
+ * sums (int64 matmul), output (float64 dequantization and LayerNorm within
+ * binary32 rounding).  The paper prints no worked example, so no stored
+ * end-to-end value exists.
  */
 #include <stdlib.h>
 #include <string.h>

@@ -18,11 +18,16 @@
  * quantizer form, where activations are quantized) follows the readings listed
  * in the design notes of this repository; each is marked "reading" below.
  *
- * Parity status: the structure is pinned by tests (float Swin block written
- * separately, uniform block written separately, brute-force mask, library
- * roll/reshape, int64 matmuls, libm exp/erf).  The numerical VALUES of a
- * quantized block output have no printed example in the paper: parity unpinned
- * for those beyond the pins listed.
+ * Parity status: every step is pinned by tests to something other than this
+ * file.  Structure: a float Swin block and a uniform block written separately,
+ * brute-force mask, library pad/roll/reshape for gather and scatter, sort for
+ * the selection.  Values, step by step from the previous step's tap: int64
+ * matmuls for every integer sum, exact rational arithmetic for every
+ * dequantize / residual / quantize epilogue on samples, float64 LayerNorm and
+ * natural-base float64 softmax for the codes they decide (equal except within
+ * a stated distance of a rounding tie), libm exp2 and erf for the two pinned
+ * routines.  The paper prints no worked example, so no stored end-to-end value
+ * exists; none of the pins is a paper-printed number.
  *
  * Layouts.  x, y: [B,H,W,C] float, channels last.  A "slot" is a position in
  * perm: slot g = b*nW + j processes window perm[b*nW+j] of image b; slots with
