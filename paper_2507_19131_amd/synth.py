@@ -94,8 +94,8 @@ QNAMES = ("a_qkv_in", "a_q", "a_k", "a_v", "a_p", "a_proj_in", "a_fc1_in", "a_fc
 DEFAULT_RANGES = {
     "a_qkv_in": (-4.0, 4.5),
     "a_q": (-1.0, 1.0),
-    "a_k": (-1.0, 1.0),
-    "a_v": (-1.0, 1.0),
+    "a_k": (-1.125, 1.125),          # q, k and v each get a range of their own, so that an exchanged quantizer shows
+    "a_v": (-0.875, 0.875),
     "a_p": (0.0, 0.3),
     "a_proj_in": (-0.4, 0.45),
     "a_fc1_in": (-4.5, 4.0),
@@ -203,6 +203,8 @@ def make_block_inputs(spec, seed, ranges=None, asymmetric=True, per_branch_bias=
         q = {}
         for name in QNAMES:
             lo, hi = ranges[name]
+            if br == 1:                                   # each branch calibrates its own step sizes (Sec. 3.2): the low
+                lo, hi = lo * 0.9375, hi * 0.9375         # branch's ranges differ also where the bit widths are equal
             sym = name in ("a_q", "a_k", "a_v") or not asymmetric
             if name == "a_p":
                 sym = False

@@ -65,7 +65,8 @@ class UBParams(C.Structure):
 def lib():
     global _lib
     if _lib is None:
-        path = build_oracle.build(force=False)
+        # ORACLE_LIBRARY_UNDER_TEST: a separately built copy (the planted-mistake test runs the pins against such copies)
+        path = os.environ.get("ORACLE_LIBRARY_UNDER_TEST") or build_oracle.build(force=False)
         L = C.CDLL(path)
         L.orc_exp2.restype = C.c_float
         L.orc_exp2.argtypes = [C.c_float]

@@ -451,6 +451,17 @@ def test_softmax_rows_and_masked_codes():
         assert abs(float(p.astype(np.float64).sum()) - 1.0) <= 1e-6
         assert np.max(np.abs(p - ref)) <= 5e-7
         assert np.all(p[40:] < 1e-30)
+    # a softmax does not change when every logit moves by the same amount: on a grid of 1/16 the differences to the
+    # row maximum are exact in binary32, so the result must be the same bits, also far outside the range of 2^x
+    grid = np.round(rng.standard_normal((16, 49)) * 48).astype(np.float32) / np.float32(16)
+    for row in grid:
+        base = np.empty(49, dtype=np.float32)
+        L.orc_softmax2(row.ctypes.data_as(O._FP), 49, base.ctypes.data_as(O._FP))
+        for offset in (-1000.0, 200.0, 1000.0):
+            moved, p = (row + np.float32(offset)).astype(np.float32), np.empty(49, dtype=np.float32)
+            assert np.array_equal((moved - np.float32(offset)), row)
+            L.orc_softmax2(moved.ctypes.data_as(O._FP), 49, p.ctypes.data_as(O._FP))
+            assert np.array_equal(p, base)
     # inside a block: every masked pair carries the code of probability zero
     spec, inp, x = _setup(14, 21, 32, 1, 3, 24)
     perm = O.select_windows(O.score_windows(inp, x), 3)
