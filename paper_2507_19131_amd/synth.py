@@ -211,8 +211,11 @@ def make_block_inputs(spec, seed, ranges=None, asymmetric=True, per_branch_bias=
             q[name] = qparam_for_range(lo, hi, bits, symmetric=sym)
         # shadow layers share weights and (unless per_branch_bias) biases across the branches
         branches.append(BranchParams(g1, b1, g2, b2, *(own_bias if per_branch_bias and br == 1 else shared_bias), q=q))
+    srng = _rng(seed, 12)                               # the scoring LayerNorm (score mode 1) has parameters of its own
+    score_gamma = np.clip(1.0 + 0.25 * srng.standard_normal(C), 0.25, 2.0).astype(np.float32)
+    score_beta = (0.1 * srng.standard_normal(C)).astype(np.float32)
     shared = SharedParams(w_qkv, w_proj, w_fc1, w_fc2, s_qkv, s_proj, s_fc1, s_fc2, rpb,
-                          score_gamma=branches[0].ln1_gamma, score_beta=branches[0].ln1_beta)
+                          score_gamma=score_gamma, score_beta=score_beta)
     return BlockInputs(spec, shared, branches)
 
 

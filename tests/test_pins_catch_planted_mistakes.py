@@ -58,6 +58,11 @@ MISTAKES = [
      "prob[j] = prob[j] * rden;", "prob[j] = prob[j];"),
     ("score is the sum of magnitudes", BLOCK,
      "acc += (double)u[ch] * (double)u[ch];", "acc += fabs((double)u[ch]);"),
+    ("scoring LayerNorm skipped", BLOCK,
+     "if (d->score_mode == 1) orc_layernorm(px,", "if (0) orc_layernorm(px,"),
+    ("score counts the padded area too (reads past the map edge clamped)", BLOCK,
+     "if (!orc_token_source(&g, w, t, &r, &c)) continue;",
+     "if (!orc_token_source(&g, w, t, &r, &c)) { r = r < d->H ? r : d->H - 1; c = c < d->W ? c : d->W - 1; }"),
     ("score taken on the shifted grid", BLOCK,
      "orc_desc g = *d; g.shift = 0;", "orc_desc g = *d;"),
     ("padded tokens enter as the LayerNorm of zeros", BLOCK,
