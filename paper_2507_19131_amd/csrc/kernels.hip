@@ -1471,9 +1471,8 @@ void launch_window(const Geom& G, const WinArgs& A, hipStream_t st)
 #define WIN_CASE(NH, HG, QS)                                                                                              \
     {                                                                                                                     \
         const dim3 grid(n_wg * HG), block(NH * QS * 64);                                                                  \
-        if (A.scores) {                                                                                                   \
-            if (A.taps) hipLaunchKernelGGL((window_kernel<NH, true, true, HG, QS>), grid, block, 0, st, G, A);            \
-            else hipLaunchKernelGGL((window_kernel<NH, false, true, HG, QS>), grid, block, 0, st, G, A);                  \
+        if (A.scores) {   /* no entry point takes scores and taps together */                                            \
+            hipLaunchKernelGGL((window_kernel<NH, false, true, HG, QS>), grid, block, 0, st, G, A);                       \
         } else {                                                                                                          \
             if (A.taps) hipLaunchKernelGGL((window_kernel<NH, true, false, HG, QS>), grid, block, 0, st, G, A);           \
             else hipLaunchKernelGGL((window_kernel<NH, false, false, HG, QS>), grid, block, 0, st, G, A);                 \

@@ -263,6 +263,30 @@ def test_forward_from_scores_matches_oracle(C, heads, shift, kh_frac, kl_frac):
     assert np.array_equal(y.cpu().numpy(), oy)
 
 
+@pytest.mark.parametrize("B,H,W,C,heads", [(1, 84, 84, 384, 12), (1, 161, 165, 192, 6), (3, 50, 57, 256, 8)])
+def test_forward_from_scores_past_the_small_map_forms(B, H, W, C, heads):
+    """The in-kernel selection in the kernel forms of larger maps: one twelve-head workgroup per window (more than
+    128 windows at C = 384), one wave per head at C = 192 (more than 512 windows), eight heads; shifted block, pruning."""
+    import oracle_api as O
+    spec, inp, x, _ = _case(B, H, W, C, heads, 3, 0.5, 43, blobs=True)
+    nW = spec.nW
+    kh, kl = int(0.4 * nW), int(0.45 * nW)
+    print("scored case", C, B * nW, "windows", flush=True)
+    dev = torch.device("cuda:0")
+    xt = torch.from_numpy(x).to(dev)
+    with gh.GpuBlock(inp) as gb:
+        scores = torch.empty((B, nW), dtype=torch.float64, device=dev)
+        M.mixaq_score_windows(gb.blk, xt, scores)
+        y = torch.full_like(xt, float("nan"))
+        perm_out = torch.full((B, nW), -1, dtype=torch.int32, device=dev)
+        M.mixaq_block_forward_scored(gb.blk, xt, scores, kh, kl, y, gb.ws, perm_out=perm_out)
+        torch.cuda.synchronize()
+    o_perm = O.select_windows(O.score_windows(inp, x), kh, k_low=kl)
+    assert np.array_equal(perm_out.cpu().numpy(), o_perm)
+    oy, _ = O.block_forward(inp, x, o_perm, kh, k_low=kl, threads=16)
+    assert np.array_equal(y.cpu().numpy(), oy)
+
+
 def test_equal_scores_are_ordered_by_window_index():
     """Windows with exactly equal scores (here: windows that are zero everywhere, and two copies of one
     window) must be ranked by their index on both sides; the block output follows."""
