@@ -39,6 +39,7 @@ SMALL = [
     (2, 3, 20, 128, 4, 0, 0.5, 25, {}),                                               # one row of windows, mostly padding
     (3, 98, 98, 192, 6, 3, 0.5, 26, {}),                                              # 588 windows at six heads: one wave per head
     (2, 84, 91, 128, 4, 3, 0.5, 28, dict(bits=(8, 2))),                               # 312 windows at four heads: one wave per head, codes four per byte
+    (2, 21, 28, 512, 16, 3, 0.4, 29, dict(bits=(7, 3))),                              # sixteen heads (FC2 with K = 2048), seven kernels
     (1, 14, 21, 1024, 32, 3, 0.5, 27, {}),                                            # the widest supported block (FC2 with K = 4096)
 ]
 
