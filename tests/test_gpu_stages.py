@@ -201,12 +201,14 @@ def test_two_chains_at_config2_shape_on_two_maps():
             gb.close()
 
 
-def test_stage_on_a_side_stream_matches_the_default_stream():
-    """All work of a call is enqueued on the stream it is given: a stage run on a second stream (default
-    priority) while the default stream is kept busy gives the same bits."""
+@pytest.mark.parametrize("B", [1, 3])
+def test_stage_on_a_side_stream_matches_the_default_stream(B):
+    """All work of a call is ordered on the stream it is given: a stage run on a second stream (default
+    priority) while the default stream is kept busy gives the same bits, and is complete as soon as that
+    stream is; with a batch also when the call runs as two chains (the second on the library's own stream)."""
     wl = synth.workload("cfg2")
     st = wl["stages"][0]
-    spec = synth.BlockSpec(1, 60, 75, 96, 3)
+    spec = synth.BlockSpec(B, 60, 75, 96, 3)
     dev = torch.device("cuda:0")
     x = torch.from_numpy(synth.make_feature_map(spec, 88, blobs=True)).to(dev)
     blocks = [gh.GpuBlock(synth.make_block_inputs(spec, 880 + i), shift) for i, shift in enumerate(st["shifts"])]
