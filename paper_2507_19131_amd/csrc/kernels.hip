@@ -1421,8 +1421,10 @@ static void launch_gemm_e(const Geom& G, const GemmArgs& A0, hipStream_t st)
     if (G.rows_total == 0) return;
     const int tiles = G.rows_total / ROW_TILE, NB = A.N / 32;
     // the activation tile through LDS, output blocks over the waves and, while the grid is small, in groups over workgroups
-    const bool half = A.K > GEMM_TILE_MAX_K && A.K <= 4096;           // a long K stays whole in LDS on 32-row tiles (K = 3072 on 19 row
-                                                                      // tiles: 16.3 us; 64-row tiles in chunks of 1024: 27.8 us)
+    // 32-row tiles: a long K stays whole in LDS (K = 3072 on 19 row tiles: 16.3 us; 64-row tiles in chunks of 1024: 27.8 us);
+    // a narrow layer on few rows gets twice the workgroups (the projection at C = 768 on 19 row tiles: 8.1 instead of 10.7 us;
+    // with 72 or 96 output blocks the wider layers have workgroups enough and lose: 13.2 and 13.8 instead of 12.4 and 13.2 us)
+    const bool half = (A.K > GEMM_TILE_MAX_K && A.K <= 4096) || (tiles <= 32 && NB <= 32 && A.K > 384 && A.K <= 1024);
     A.kchunk = A.K;
     if (A.K > 4096)                                                   // chunks of whole ring turns (256 bytes of K each): the largest such size up to
         for (A.kchunk = 1024; A.kchunk > 256 && A.K % A.kchunk; A.kchunk -= 256) {}   // 1024 that divides K (K = 768 r or 1024 r here: 256 always does)
@@ -1430,7 +1432,8 @@ static void launch_gemm_e(const Geom& G, const GemmArgs& A0, hipStream_t st)
     const int groups = std::max(1, std::min((NB + 3) / 4, (512 + nt - 1) / nt));
     A.nb_per_block = ((NB + groups - 1) / groups + 3) / 4 * 4;
     const dim3 grid(nt, (NB + A.nb_per_block - 1) / A.nb_per_block);
-    if (half && A.K <= 3072) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 3072, 32>), grid, dim3(256), 0, st, G, A);
+    if (half && A.K <= 1024) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 1024, 32>), grid, dim3(256), 0, st, G, A);
+    else if (half && A.K <= 3072) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 3072, 32>), grid, dim3(256), 0, st, G, A);
     else if (half) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 4096, 32>), grid, dim3(256), 0, st, G, A);
     else if (A.K <= 384) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 384>), grid, dim3(256), 0, st, G, A);
     else if (A.K <= 1024 || A.K > GEMM_TILE_MAX_K) hipLaunchKernelGGL((gemm_tile_kernel<EPI, 1024>), grid, dim3(256), 0, st, G, A);   // above 4096: chunks of 1024
