@@ -391,7 +391,7 @@ int forward_impl(const mixaq_block* blk, const float* x, const int32_t* perm, co
     // ---- first half: gather + LN1 + quantize, QKV, windowed attention -> attention-output codes, row bookkeeping
     if (fw) {
         WinArgs wa = {};
-        wa.x = x; wa.perm = perm; wa.scores = in_kernel_select ? scores : nullptr; wa.reverse = 0; wa.perm_out = perm_out ? perm_out : ws.perm;
+        wa.x = x; wa.perm = perm; wa.scores = in_kernel_select ? scores : nullptr; wa.perm_out = perm_out ? perm_out : ws.perm;
         wa.y = y; wa.eps = d.ln_eps; wa.Wqkv = blk->qkv.Wp; wa.bias2 = blk->bias2; wa.out = ws.ao;
         wa.row_pix = ws.row_pix; wa.row_canon = ws.row_canon;
         wa.out_pack = ft ? blk->ao_pack : 0;

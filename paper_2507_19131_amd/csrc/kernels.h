@@ -70,7 +70,6 @@ struct WinArgs {                     // fused window kernel (gather + LN1 + QKV 
     const float* x;
     const int* perm;                 // selection list, or ...
     const double* scores;            // ... the scores: every workgroup ranks its own window ([B,nW]; NULL = use perm)
-    int reverse;                     // with scores: invert the order of importance
     int* perm_out;                   // with scores: receives the selection list
     float* y;                        // with scores: pruned windows are forwarded here
     // per branch one block of 32-bit words, staged in LDS by every workgroup:

@@ -691,7 +691,7 @@ __global__ __launch_bounds__(NH * QS * 64) __attribute__((amdgpu_waves_per_eu(wi
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 const int u = base + tid + k * NT;
-                cnt += (u < G.nW && ranked_before(sv[k], u, sw, w, A.reverse)) ? 1 : 0;
+                cnt += (u < G.nW && ranked_before(sv[k], u, sw, w, 0)) ? 1 : 0;
             }
         }
 #pragma unroll
