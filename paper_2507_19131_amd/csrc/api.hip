@@ -501,8 +501,31 @@ int mixaq_keep_count(int32_t nW, double keep_ratio, int32_t* k_high)
     return MIXAQ_OK;
 }
 
+static int block_create(const mixaq_block_desc* desc, const mixaq_shared_params* sh, const mixaq_branch_params branch[2],
+                        void* stream, mixaq_block** out);
+
+// No C++ exception leaves the library: host containers that fail to allocate become an error code.
 int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* sh, const mixaq_branch_params branch[2],
                        void* stream, mixaq_block** out)
+{
+    try {
+        return block_create(desc, sh, branch, stream, out);
+    } catch (const std::bad_alloc&) {
+        return fail(MIXAQ_E_HIP, "out of host memory while preparing the block");
+    } catch (...) {
+        return fail(MIXAQ_E_HIP, "unexpected C++ exception while preparing the block");
+    }
+}
+
+namespace {
+struct BlockOwner {                      // destroys a half-built block on every early return and on an exception
+    mixaq_block* b;
+    ~BlockOwner() { if (b) mixaq_block_destroy(b); }
+};
+}  // namespace
+
+static int block_create(const mixaq_block_desc* desc, const mixaq_shared_params* sh, const mixaq_branch_params branch[2],
+                        void* stream, mixaq_block** out)
 {
     int rc = check_desc(desc);
     if (rc) return rc;
@@ -528,7 +551,8 @@ int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* 
     b->Hp = round_up(desc->H, WS); b->Wp = round_up(desc->W, WS);
     b->nWc = b->Wp / WS; b->nW = (b->Hp / WS) * b->nWc;
     const int C = desc->C, F = C * desc->mlp_ratio, heads = desc->heads;
-    auto bail = [&](int code) { mixaq_block_destroy(b); return code; };
+    BlockOwner owner{b};
+    auto bail = [&](int code) { return code; };          // the owner destroys the block
     mixaq_qparam qi[2];
     const float* bias[2];
     qi[0] = branch[0].a_qkv_in; qi[1] = branch[1].a_qkv_in; bias[0] = branch[0].b_qkv; bias[1] = branch[1].b_qkv;
@@ -649,6 +673,7 @@ int mixaq_block_create(const mixaq_block_desc* desc, const mixaq_shared_params* 
             hipEventCreateWithFlags(&b->ev_join, hipEventDisableTiming) != hipSuccess)
             return bail(fail(MIXAQ_E_HIP, "creating the second stream of the stage failed"));
     }
+    owner.b = nullptr;
     *out = b;
     return MIXAQ_OK;
 }

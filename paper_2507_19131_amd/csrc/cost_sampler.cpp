@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstddef>
 #include <cstdint>
+#include <new>
 #include <numeric>
 #include <vector>
 
@@ -88,8 +89,24 @@ struct Apportion {
 };
 }  // namespace
 
+static int sample_ratios(int32_t n, double s_min, double s_max, double upper, const double* uniforms, size_t n_uniforms,
+                         size_t* n_used, double* ratios);
+
+// No C++ exception leaves the library: host containers that fail to allocate become an error code.
 extern "C" int mixaq_sample_ratios(int32_t n, double s_min, double s_max, double upper, const double* uniforms, size_t n_uniforms,
                                    size_t* n_used, double* ratios)
+{
+    try {
+        return sample_ratios(n, s_min, s_max, upper, uniforms, n_uniforms, n_used, ratios);
+    } catch (const std::bad_alloc&) {
+        return fail(MIXAQ_E_HIP, "out of host memory while sampling %d ratios", n);
+    } catch (...) {
+        return fail(MIXAQ_E_HIP, "unexpected C++ exception while sampling");
+    }
+}
+
+static int sample_ratios(int32_t n, double s_min, double s_max, double upper, const double* uniforms, size_t n_uniforms,
+                         size_t* n_used, double* ratios)
 {
     if (!uniforms || !ratios) return fail(MIXAQ_E_NULL, "uniforms or ratios is NULL");
     if (n < 1 || !(s_min >= 0.0) || !(s_max >= s_min) || !(upper > 0.0) || upper > 1.0)

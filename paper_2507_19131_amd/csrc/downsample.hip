@@ -395,7 +395,28 @@ int mixaq_downsample_out_shape(const mixaq_downsample_desc* desc, int32_t* Ho, i
     return MIXAQ_OK;
 }
 
+static int downsample_create(const mixaq_downsample_desc* desc, const mixaq_downsample_params* p, mixaq_downsample** out);
+
+// No C++ exception leaves the library: host containers that fail to allocate become an error code.
 int mixaq_downsample_create(const mixaq_downsample_desc* desc, const mixaq_downsample_params* p, mixaq_downsample** out)
+{
+    try {
+        return downsample_create(desc, p, out);
+    } catch (const std::bad_alloc&) {
+        return fail(MIXAQ_E_HIP, "out of host memory while preparing the layer");
+    } catch (...) {
+        return fail(MIXAQ_E_HIP, "unexpected C++ exception while preparing the layer");
+    }
+}
+
+namespace {
+struct LayerOwner {                      // frees a half-built layer on every early return and on an exception
+    mixaq_downsample* h;
+    ~LayerOwner() { delete h; }
+};
+}  // namespace
+
+static int downsample_create(const mixaq_downsample_desc* desc, const mixaq_downsample_params* p, mixaq_downsample** out)
 {
     if (!out) return fail(MIXAQ_E_NULL, "out is NULL");
     *out = nullptr;
@@ -410,7 +431,8 @@ int mixaq_downsample_create(const mixaq_downsample_desc* desc, const mixaq_downs
     if ((size_t)Kp * 32 > 64 * 1024) return fail(MIXAQ_E_SHAPE, "too many inputs per token for one workgroup's LDS");
     mixaq_downsample* h = new (std::nothrow) mixaq_downsample();
     if (!h) return fail(MIXAQ_E_HIP, "out of host memory");
-    auto bail = [&](int code) { delete h; return code; };
+    LayerOwner owner{h};
+    auto bail = [&](int code) { return code; };          // the owner frees the layer
     h->d = *desc; h->P = P; h->K = K; h->Kp = Kp; h->Ho = Ho; h->Wo = Wo;
     std::vector<int8_t> w((size_t)N * K);
     std::vector<float> s(N), bias(N, 0.0f), ln_g(n_ln), ln_b(n_ln);
@@ -454,6 +476,7 @@ int mixaq_downsample_create(const mixaq_downsample_desc* desc, const mixaq_downs
     h->q.magic = RND_MAGIC + (float)p->a_in.zero_point;
     h->q.lo = RND_MAGIC + (float)qmin;
     h->q.hi = RND_MAGIC + (float)qmax;
+    owner.h = nullptr;
     *out = h;
     return MIXAQ_OK;
 }
