@@ -752,6 +752,14 @@ int mixaq_stage_forward(mixaq_block* const* blocks, int32_t n_blocks, const floa
         if (a.B != b.B || a.H != b.H || a.W != b.W || a.C != b.C)
             return fail(MIXAQ_E_SHAPE, "blocks[%d] was created for another map shape", i);
     }
+    {   // the blocks alternate between tmp and y while later blocks (or the other chain) may still read x
+        const mixaq_block_desc& d0 = blocks[0]->d;
+        const size_t bytes = (size_t)d0.B * d0.H * d0.W * d0.C * 4;
+        auto overlap = [&](const float* a, const float* c) {
+            return a && c && (const char*)a < (const char*)c + bytes && (const char*)c < (const char*)a + bytes;
+        };
+        if (overlap(x, y) || overlap(x, tmp) || overlap(y, tmp)) return fail(MIXAQ_E_SHAPE, "x, y and tmp must not overlap");
+    }
     const int nW = blocks[0]->nW;
     for (int p = 0; p < (n_blocks + 1) / 2; ++p) {
         const int kh = k_high[p], kl = k_low ? k_low[p] : nW - kh;

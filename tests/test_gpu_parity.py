@@ -209,6 +209,19 @@ def test_error_paths_do_not_launch():
         with pytest.raises(M.MixaqError) as e:
             M.mixaq_block_forward(gb.blk, xt, None, k, xt, gb.ws)
         assert e.value.code == -2
+        # the stage call: x, y and tmp must be three separate maps; blocks of another shape are refused
+        scores = torch.empty((1, spec.nW), dtype=torch.float64, device="cuda")
+        perm = torch.empty((1, spec.nW), dtype=torch.int32, device="cuda")
+        tmp = torch.empty_like(xt)
+        for bad in ((xt, xt, tmp), (xt, y, y), (xt, y, xt)):
+            with pytest.raises(M.MixaqError) as e:
+                M.mixaq_stage_forward([gb.blk, gb.blk], bad[0], [k], None, bad[1], bad[2], scores, perm, gb.ws)
+            assert e.value.code == -2
+        with pytest.raises(M.MixaqError) as e:
+            M.mixaq_stage_forward([gb.blk, gb.blk], xt, [spec.nW + 1], None, y, tmp, scores, perm, gb.ws)
+        assert e.value.code == -2
+        M.mixaq_stage_forward([gb.blk, gb.blk], xt, [k], None, y, tmp, scores, perm, gb.ws)      # and the good call still runs
+        torch.cuda.synchronize()
 
 
 @pytest.mark.parametrize("fused", [True, False])
