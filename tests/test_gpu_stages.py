@@ -278,6 +278,84 @@ def test_stage_call_as_the_benchmark_launches_it(name, stage):
     assert np.array_equal(y_gpu, cur)
 
 
+def test_random_sweep_of_stage_calls():
+    """Thirty seeded random stage calls: width, batch (one or two chains), map size, 1-4 blocks, bit widths, score mode,
+    shared or independent biases and, per pair, any split into high, low and pruned windows (none and all included);
+    maps and selection lists must equal the oracle's bit for bit."""
+    dev = torch.device("cuda:0")
+    for case in range(30):
+        rng = np.random.default_rng(61000 + case)
+        C, heads = [(96, 3), (128, 4), (192, 6), (256, 8), (384, 12)][int(rng.choice([0, 0, 1, 2, 3, 4]))]
+        B, H, W = int(rng.integers(1, 7)), int(rng.integers(14, 60)), int(rng.integers(14, 60))
+        shifts = [0, 3, 0, 3][:int(rng.integers(1, 5))]
+        hi = int(rng.integers(4, 9))
+        spec = synth.BlockSpec(B, H, W, C, heads, act_bits_high=hi, act_bits_low=int(rng.integers(2, hi + 1)),
+                               weight_bits=int(rng.choice([4, 8])), score_mode=int(rng.integers(0, 2)))
+        k_high, k_low = [], []
+        for _ in range((len(shifts) + 1) // 2):
+            kh = int(rng.integers(0, spec.nW + 1))
+            kl = int(rng.integers(0, spec.nW - kh + 1))
+            if rng.integers(0, 2):
+                kl = spec.nW - kh                                   # no pruning
+            k_high.append(kh)
+            k_low.append(kl)
+        print("stage sweep case", case, "B", B, H, W, "C", C, "blocks", len(shifts), "k_high", k_high, "k_low", k_low, flush=True)
+        x_np = synth.make_feature_map(spec, 62000 + case, blobs=bool(rng.integers(0, 2)))
+        inputs = [synth.make_block_inputs(spec, 63000 + 10 * case + i, per_branch_bias=bool(rng.integers(0, 2))) for i in range(len(shifts))]
+        x = torch.from_numpy(x_np).to(dev)
+        blocks = [gh.GpuBlock(inp, shift) for inp, shift in zip(inputs, shifts)]
+        try:
+            y, tmp = torch.full_like(x, float("nan")), torch.empty_like(x)
+            scores = torch.empty((B, spec.nW), dtype=torch.float64, device=dev)
+            perm = torch.full((B, spec.nW), -1, dtype=torch.int32, device=dev)
+            for _ in range(2):
+                M.mixaq_stage_forward([gb.blk for gb in blocks], x, k_high, k_low, y, tmp, scores, perm, blocks[0].ws)
+            torch.cuda.synchronize()
+            y_gpu, perm_gpu = y.cpu().numpy(), perm.cpu().numpy()
+        finally:
+            for gb in blocks:
+                gb.close()
+        sc_o = O.score_windows(inputs[0], x_np)
+        cur = x_np
+        for i, (inp, shift) in enumerate(zip(inputs, shifts)):
+            perm_o = O.select_windows(sc_o, k_high[i // 2], k_low=k_low[i // 2])
+            cur, _ = O.block_forward(inp, cur, perm_o, k_high[i // 2], shift, threads=16, k_low=k_low[i // 2])
+        assert np.array_equal(perm_gpu, perm_o), case
+        assert np.array_equal(y_gpu, cur), case
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3"])
+def test_repeated_stage_calls_are_bit_stable(name):
+    """The same stage call a hundred times over (one chain at config 2, two chains at config 3): every result has the
+    bits of the first, which a missing barrier or a race between the chains would not survive."""
+    wl = synth.workload(name)
+    st = wl["stages"][0]
+    spec, shifts = st["spec"], st["shifts"]
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(synth.make_feature_map(spec, wl["seed"], blobs=wl["blobs"], outlier_channels=wl["outliers"])).to(dev)
+    blocks = [gh.GpuBlock(synth.make_block_inputs(spec, wl["seed"] + 10 * i, ranges=wl.get("ranges")), shift) for i, shift in enumerate(shifts)]
+    try:
+        k = M.mixaq_keep_count(spec.nW, 0.5)
+        pairs = (len(shifts) + 1) // 2
+        y, tmp = torch.empty_like(x), torch.empty_like(x)
+        scores = torch.empty((spec.B, spec.nW), dtype=torch.float64, device=dev)
+        perm = torch.empty((spec.B, spec.nW), dtype=torch.int32, device=dev)
+        handles = [gb.blk for gb in blocks]
+        M.mixaq_stage_forward(handles, x, [k] * pairs, None, y, tmp, scores, perm, blocks[0].ws)
+        torch.cuda.synchronize()
+        first, first_perm = y.clone(), perm.clone()
+        print("repeating the stage call of", name, flush=True)
+        for it in range(100):
+            y.fill_(float("nan"))
+            M.mixaq_stage_forward(handles, x, [k] * pairs, None, y, tmp, scores, perm, blocks[0].ws)
+            if it % 5 == 4:
+                assert torch.equal(y, first) and torch.equal(perm, first_perm), it
+        torch.cuda.synchronize()
+    finally:
+        for gb in blocks:
+            gb.close()
+
+
 def test_stage_call_can_be_captured_in_a_graph():
     """The stage call allocates nothing and never synchronises, so a caller may capture it; every replay, with
     eager work and synchronisations in between, reproduces the eager result."""
